@@ -1,0 +1,158 @@
+/*
+ * hgf.h -- C ABI of the MI355X (gfx950) HGF linear-layer library.
+ *
+ * The library computes the inference forward pass of one Hybrid Gated Flow linear
+ * layer (Algorithm 1, "HGF 1.0 Forward Pass, Inference Mode"):
+ *
+ *     y[m, n] = s_x[m] * s_w * sum_k T[n, k] * x_q[m, k]
+ *             + tanh(alpha[n]) * sum_j B[n, j] * SiLU( sum_k A[j, k] * x[m, k] )
+ *
+ * with T in {-1, 0, +1} the absmean-ternarised weights (2 bits each, packed),
+ * x_q the per-token absmax int8 quantisation of the fp16 activations x, and A, B,
+ * alpha the fp16 low-rank correction path and its gate.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless it is
+ *     marked "host".  The library never allocates, frees or keeps a pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
+ *     only enqueues kernels on that stream: no synchronisation, no host read-back.
+ *   - Arguments are validated on the host before anything is enqueued; on error
+ *     nothing has been launched and a non-zero hgf_status is returned.
+ *   - Matrices are row-major.  fp16 tensors are IEEE binary16, passed as void*.
+ *   - Limits: 1 <= d_in, d_out <= 65536; rank in {0} u [1, 128]; M >= 1 with
+ *     M * max(d_in, d_out) < 2^31; packed weights, x_q, x and y 16-byte aligned.
+ */
+#ifndef HGF_H
+#define HGF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HGF_OK = 0,
+    HGF_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    HGF_ERR_SHAPE = 2,       /* a dimension is out of the supported range           */
+    HGF_ERR_ALIGN = 3,       /* a buffer is not 16-byte aligned                     */
+    HGF_ERR_UNSUPPORTED = 4, /* valid request this build does not implement         */
+    HGF_ERR_WORKSPACE = 5,   /* workspace missing or smaller than hgf_workspace_bytes */
+    HGF_ERR_DEVICE = 6       /* the HIP runtime refused a launch                    */
+} hgf_status;
+
+#define HGF_MAX_RANK 128
+#define HGF_MAX_DIM 65536
+
+/* Human-readable name of a status code (static storage, host). */
+const char *hgf_status_string(int status);
+/* Library version, major*10000 + minor*100 + patch. */
+int hgf_version(void);
+
+/* ---------------------------------------------------------------- sizes (host only) */
+
+/* d_in rounded up to the packing granule (64).  Rows of x_q have this many bytes;
+ * the padding bytes are written as 0 by hgf_quantize_activations. */
+int hgf_padded_k(int d_in);
+/* Bytes of the packed 2-bit weight buffer of a [d_out, d_in] matrix (both
+ * dimensions padded to 64; padding decodes to 0).  0 on invalid sizes. */
+size_t hgf_packed_weight_bytes(int d_out, int d_in);
+/* Bytes of workspace that any call with M <= M_max, d_in <= d_in_max,
+ * d_out <= d_out_max, rank <= rank_max needs.  0 on invalid sizes. */
+size_t hgf_workspace_bytes(int M_max, int d_in_max, int d_out_max, int rank_max);
+
+/* Clears a workspace.  Must be called once (and again after any call that returned
+ * HGF_ERR_DEVICE) before the workspace is used: the forward calls keep a region of
+ * split-K accumulators and arrival counters that they expect to find zero and leave
+ * zero.  A workspace serves one call at a time: calls that share one must be
+ * ordered on a single stream. */
+hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------- weights (offline)
+ *
+ * Absmean ternarisation (Sec. 2.2, weight-quantisation definition; the paper's own
+ * implementation fixes the details): gamma_W = max(mean |W|, 1e-5), the mean taken in
+ * fp64 and rounded once to fp32; T = clip(round_half_even(W * (1/gamma_W)), -1, 1) in
+ * fp32.  Writes the packed codes and the scalar s_w = gamma_W.
+ *
+ *   W          fp32 [d_out, d_in]
+ *   packed_out hgf_packed_weight_bytes(d_out, d_in) bytes
+ *   s_w_out    one fp32
+ *
+ * Packed layout: tiles of 64 rows x 64 columns, 1 KiB each, ordered row-block major
+ * then along d_in, so one row-block's tiles are contiguous.  Within a tile, byte
+ * 16*l + 4*q .. +3 (l = 0..63, q = 0..3) is a little-endian 32-bit word holding the 16
+ * codes of row 16*q + (l mod 16), columns 16*(l div 16) + 0..15; column offset 4*s + b
+ * sits at bits [8*b + 2*s, 8*b + 2*s + 1].  A code is T + 1 (0, 1 or 2; 3 never
+ * occurs); padding rows and columns hold code 1.
+ */
+hgf_status hgf_quantize_pack_weights(const float *W, int d_out, int d_in, void *packed_out,
+                                     float *s_w_out, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
+/* Inverse of the packed layout: T_out int8 [d_out, d_in] with values -1, 0, +1. */
+hgf_status hgf_unpack_weights(const void *packed, int d_out, int d_in, int8_t *T_out,
+                              void *stream);
+
+/* ---------------------------------------------------------------- activations
+ *
+ * Per-token absmax int8 quantisation (Sec. 2.2.1; Algorithm 1, steps 1-2):
+ * amax = max(max_k |x[m, k]|, 1e-5); x_q = clip(round_half_even(x * (127/amax)), -127,
+ * 127) in fp32; s_x[m] = amax / 127.
+ *
+ *   x_f16      fp16 [M, d_in]
+ *   xq_out     int8 [M, hgf_padded_k(d_in)]   (padding columns = 0)
+ *   s_x_out    fp32 [M]
+ *   rowsum_out int32 [M] = sum_k x_q[m, k]; may be NULL
+ */
+hgf_status hgf_quantize_activations(const void *x_f16, int M, int d_in, int8_t *xq_out,
+                                    float *s_x_out, int32_t *rowsum_out, void *stream);
+
+/* ---------------------------------------------------------------- one layer */
+
+typedef struct {
+    int d_in, d_out;
+    int rank;               /* 0: no correction path (A, B, alpha ignored): a pure ternary layer */
+    const void *W_packed;   /* from hgf_quantize_pack_weights                                     */
+    const float *s_w;       /* device scalar gamma_W                                              */
+    const void *A_f16;      /* fp16 [rank, d_in]   down-projection                                */
+    const void *B_f16;      /* fp16 [d_out, rank]  up-projection                                  */
+    const void *alpha_f16;  /* fp16 [d_out]        gate parameter, g = tanh(alpha)                */
+    int src_slot, dst_slot; /* used only by hgf_stack_forward                                     */
+} hgf_layer;
+
+/* Algorithm 1, steps 1-8, for one layer.
+ *
+ *   x_f16     fp16 [M, d_in]
+ *   L         host pointer to the layer description (its pointers are device pointers)
+ *   y_f16     fp16 [M, d_out], written
+ *   acc_debug int32 [M, d_out] or NULL: receives the exact integer accumulators
+ *             sum_k T[n,k] x_q[m,k] of step 3 (for parity tests)
+ *
+ * M <= 64 runs the bandwidth-bound decode kernel (weights streamed once); larger M
+ * runs the int8 MFMA prefill kernel.  Both give the same integers. */
+hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void *y_f16,
+                              int32_t *acc_debug, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
+/* A list of layers run in order on one stream.  Layer i reads slots[src_slot] (fp16
+ * [M, d_in]) and writes slots[dst_slot] (fp16 [M, d_out]); consecutive layers with the
+ * same src_slot and d_in share one activation quantisation (the q/k/v and up/gate
+ * projections of a transformer block read the same input).
+ *
+ *   layers  host array of n_layers descriptions
+ *   slots   host array of n_slots device pointers
+ */
+hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const *slots,
+                             int n_slots, int M, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+/* Tuning hook for benchmarks (host state, not thread-safe): how many decode workgroups a
+ * launch aims at when it splits d_in across workgroups; 0 restores the default. */
+void hgf_set_decode_target_workgroups(int n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGF_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of libhgf.so: the same entry points as include/hgf.h, taking torch
+tensors.  Argument marshalling only -- every step of the layer runs in the HIP kernels;
+torch provides device memory and the stream.  There is no fallback: a missing library
+is an error."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhgf.so")
+
+HGF_OK = 0
+STATUS_NAMES = {0: "HGF_OK", 1: "HGF_ERR_NULL", 2: "HGF_ERR_SHAPE", 3: "HGF_ERR_ALIGN",
+                4: "HGF_ERR_UNSUPPORTED", 5: "HGF_ERR_WORKSPACE", 6: "HGF_ERR_DEVICE"}
+
+
+class HgfError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().hgf_status_string(status).decode()} (status {status})")
+
+
+class hgf_layer(ctypes.Structure):
+    _fields_ = [("d_in", ctypes.c_int), ("d_out", ctypes.c_int), ("rank", ctypes.c_int),
+                ("W_packed", ctypes.c_void_p), ("s_w", ctypes.c_void_p),
+                ("A_f16", ctypes.c_void_p), ("B_f16", ctypes.c_void_p), ("alpha_f16", ctypes.c_void_p),
+                ("src_slot", ctypes.c_int), ("dst_slot", ctypes.c_int)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_05269_amd.build` "
+                           "(there is no CPU or PyTorch fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.hgf_status_string.restype = ctypes.c_char_p
+    L.hgf_status_string.argtypes = [ci]
+    L.hgf_version.restype = ci
+    L.hgf_padded_k.restype = ci
+    L.hgf_padded_k.argtypes = [ci]
+    L.hgf_packed_weight_bytes.restype = sz
+    L.hgf_packed_weight_bytes.argtypes = [ci, ci]
+    L.hgf_workspace_bytes.restype = sz
+    L.hgf_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    L.hgf_workspace_init.restype = ci
+    L.hgf_workspace_init.argtypes = [vp, sz, vp]
+    L.hgf_quantize_pack_weights.restype = ci
+    L.hgf_quantize_pack_weights.argtypes = [vp, ci, ci, vp, vp, vp, sz, vp]
+    L.hgf_unpack_weights.restype = ci
+    L.hgf_unpack_weights.argtypes = [vp, ci, ci, vp, vp]
+    L.hgf_quantize_activations.restype = ci
+    L.hgf_quantize_activations.argtypes = [vp, ci, ci, vp, vp, vp, vp]
+    L.hgf_linear_forward.restype = ci
+    L.hgf_linear_forward.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp, sz, vp]
+    L.hgf_stack_forward.restype = ci
+    L.hgf_stack_forward.argtypes = [ctypes.POINTER(hgf_layer), ci, ctypes.POINTER(vp), ci, ci, vp, sz, vp]
+    L.hgf_set_decode_target_workgroups.restype = None
+    L.hgf_set_decode_target_workgroups.argtypes = [ci]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != HGF_OK:
+        raise HgfError(status, where)
+
+
+def _stream(stream: Optional[torch.cuda.Stream] = None) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor in device memory")
+    return t
+
+
+# --------------------------------------------------------------------------- sizes
+
+def hgf_version() -> int:
+    return lib().hgf_version()
+
+
+def hgf_padded_k(d_in: int) -> int:
+    return lib().hgf_padded_k(d_in)
+
+
+def hgf_packed_weight_bytes(d_out: int, d_in: int) -> int:
+    return lib().hgf_packed_weight_bytes(d_out, d_in)
+
+
+def hgf_workspace_bytes(M_max: int, d_in_max: int, d_out_max: int, rank_max: int) -> int:
+    return lib().hgf_workspace_bytes(M_max, d_in_max, d_out_max, rank_max)
+
+
+class Workspace:
+    """A device buffer of hgf_workspace_bytes, cleared by hgf_workspace_init."""
+
+    def __init__(self, M_max: int, d_in_max: int, d_out_max: int, rank_max: int, device="cuda"):
+        n = hgf_workspace_bytes(M_max, d_in_max, d_out_max, rank_max)
+        if n == 0:
+            raise ValueError("invalid workspace dimensions")
+        self.buf = torch.empty(n, dtype=torch.uint8, device=device)
+        self.bytes = n
+        hgf_workspace_init(self)
+
+
+def hgf_workspace_init(ws: Workspace, stream=None) -> None:
+    _check(lib().hgf_workspace_init(ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_workspace_init")
+
+
+def hgf_set_decode_target_workgroups(n: int) -> None:
+    lib().hgf_set_decode_target_workgroups(n)
+
+
+# --------------------------------------------------------------------------- steps
+
+def hgf_quantize_pack_weights(W: torch.Tensor, ws: Workspace, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp32 [d_out, d_in] -> (packed uint8 buffer, s_w fp32 scalar tensor)."""
+    _dev(W, torch.float32, "W")
+    d_out, d_in = W.shape
+    packed = torch.empty(hgf_packed_weight_bytes(d_out, d_in), dtype=torch.uint8, device=W.device)
+    s_w = torch.empty(1, dtype=torch.float32, device=W.device)
+    _check(lib().hgf_quantize_pack_weights(W.data_ptr(), d_out, d_in, packed.data_ptr(), s_w.data_ptr(),
+                                           ws.buf.data_ptr(), ws.bytes, _stream(stream)),
+           "hgf_quantize_pack_weights")
+    return packed, s_w
+
+
+def hgf_unpack_weights(packed: torch.Tensor, d_out: int, d_in: int, stream=None) -> torch.Tensor:
+    T = torch.empty((d_out, d_in), dtype=torch.int8, device=packed.device)
+    _check(lib().hgf_unpack_weights(packed.data_ptr(), d_out, d_in, T.data_ptr(), _stream(stream)),
+           "hgf_unpack_weights")
+    return T
+
+
+def hgf_quantize_activations(x: torch.Tensor, stream=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """fp16 [M, d_in] -> (x_q int8 [M, padded_k], s_x fp32 [M], rowsum int32 [M])."""
+    _dev(x, torch.float16, "x")
+    M, d_in = x.shape
+    xq = torch.empty((M, hgf_padded_k(d_in)), dtype=torch.int8, device=x.device)
+    s_x = torch.empty(M, dtype=torch.float32, device=x.device)
+    rowsum = torch.empty(M, dtype=torch.int32, device=x.device)
+    _check(lib().hgf_quantize_activations(x.data_ptr(), M, d_in, xq.data_ptr(), s_x.data_ptr(),
+                                          rowsum.data_ptr(), _stream(stream)), "hgf_quantize_activations")
+    return xq, s_x, rowsum
+
+
+class Layer:
+    """Device tensors of one HGF linear plus the hgf_layer record that points at them."""
+
+    def __init__(self, packed: torch.Tensor, s_w: torch.Tensor, d_out: int, d_in: int,
+                 A: Optional[torch.Tensor] = None, B: Optional[torch.Tensor] = None,
+                 alpha: Optional[torch.Tensor] = None, src_slot: int = 0, dst_slot: int = 1):
+        self.packed, self.s_w, self.A, self.B, self.alpha = packed, s_w, A, B, alpha
+        rank = 0 if A is None else A.shape[0]
+        if rank:
+            _dev(A, torch.float16, "A"), _dev(B, torch.float16, "B"), _dev(alpha, torch.float16, "alpha")
+            if tuple(A.shape) != (rank, d_in) or tuple(B.shape) != (d_out, rank) or tuple(alpha.shape) != (d_out,):
+                raise ValueError("A must be [rank, d_in], B [d_out, rank], alpha [d_out]")
+        if packed.numel() != hgf_packed_weight_bytes(d_out, d_in):
+            raise ValueError("packed buffer has the wrong size for these dimensions")
+        self.d_in, self.d_out, self.rank = d_in, d_out, rank
+        self.c = hgf_layer(d_in, d_out, rank, packed.data_ptr(), s_w.data_ptr(), _ptr(A), _ptr(B), _ptr(alpha),
+                           src_slot, dst_slot)
+
+    @classmethod
+    def from_latent(cls, W: torch.Tensor, A, B, alpha, ws: Workspace, **kw) -> "Layer":
+        packed, s_w = hgf_quantize_pack_weights(W, ws)
+        return cls(packed, s_w, W.shape[0], W.shape[1], A, B, alpha, **kw)
+
+
+def hgf_linear_forward(x: torch.Tensor, layer: Layer, ws: Workspace, y: Optional[torch.Tensor] = None,
+                       acc_debug: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """One HGF linear: fp16 [M, d_in] -> fp16 [M, d_out] (written into `y` when given)."""
+    _dev(x, torch.float16, "x")
+    M, d_in = x.shape
+    if d_in != layer.d_in:
+        raise ValueError("x has the wrong d_in")
+    if y is None:
+        y = torch.empty((M, layer.d_out), dtype=torch.float16, device=x.device)
+    _check(lib().hgf_linear_forward(x.data_ptr(), M, ctypes.byref(layer.c), y.data_ptr(), _ptr(acc_debug),
+                                    ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_linear_forward")
+    return y
+
+
+class Stack:
+    """A layer list and its slot table, marshalled once so a forward is one C call."""
+
+    def __init__(self, layers: Sequence[Layer], slots: Sequence[torch.Tensor], M: int):
+        self.layers, self.slots, self.M = list(layers), list(slots), M
+        self.c_layers = (hgf_layer * len(layers))(*[l.c for l in layers])
+        self.c_slots = (ctypes.c_void_p * len(slots))(*[s.data_ptr() for s in slots])
+
+
+def hgf_stack_forward(stack: Stack, ws: Workspace, stream=None) -> None:
+    _check(lib().hgf_stack_forward(stack.c_layers, len(stack.layers), stack.c_slots, len(stack.slots), stack.M,
+                                   ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_stack_forward")

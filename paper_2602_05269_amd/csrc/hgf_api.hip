@@ -1,0 +1,212 @@
+// C ABI of libhgf: host-side argument validation, workspace carving and dispatch.
+// Every check happens before the first HIP call, so the error paths run without a GPU.
+#include "hgf_internal.h"
+
+namespace hgf {
+
+Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
+{
+    Workspace ws;
+    char *p = reinterpret_cast<char *>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *r = p ? p + off : nullptr;
+        off += align256(bytes);
+        return r;
+    };
+    ws.acc = reinterpret_cast<int32_t *>(take(kAccZeroBytes));
+    ws.counters = reinterpret_cast<int32_t *>(take(size_t(kNumCounters) * 4));
+    const int Kp = round_up(d_in, kTile);
+    ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
+    ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
+    ws.rowsum = reinterpret_cast<int32_t *>(take((size_t)M * 4));
+    ws.h16 = reinterpret_cast<_Float16 *>(take((size_t)M * h_stride(rank > 0 ? rank : 1) * 2));
+    // scratch for the partial sums of the down-projection: a bound that is monotone in M and
+    // rank (the launcher uses at most min(32, ceil(768/tiles)) slices over `tiles` token tiles)
+    const size_t hpart = rank > 0 ? (size_t)(768 + (M + 15) / 16) * h_rank_tiles(rank) * 64 * 16 : 0;
+    ws.hpart = reinterpret_cast<float *>(take(hpart));
+    ws.wsum = reinterpret_cast<double *>(take(size_t(kWsumBlocks) * 8));
+    (void)d_out;
+    ws.bytes = off;
+    return ws;
+}
+
+namespace {
+
+bool dims_ok(int d_in, int d_out) { return d_in >= 1 && d_out >= 1 && d_in <= HGF_MAX_DIM && d_out <= HGF_MAX_DIM; }
+bool tokens_ok(int M, int d_in, int d_out)
+{
+    if (M < 1) return false;
+    const long long big = (long long)M * (d_in > d_out ? d_in : d_out);
+    return big < (1LL << 31);
+}
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+hgf_status check_layer(const hgf_layer *L, int M)
+{
+    if (!L) return HGF_ERR_NULL;
+    if (!dims_ok(L->d_in, L->d_out) || L->rank < 0 || L->rank > HGF_MAX_RANK) return HGF_ERR_SHAPE;
+    if (!tokens_ok(M, L->d_in, L->d_out)) return HGF_ERR_SHAPE;
+    if (!L->W_packed || !L->s_w) return HGF_ERR_NULL;
+    if (L->rank > 0 && (!L->A_f16 || !L->B_f16 || !L->alpha_f16)) return HGF_ERR_NULL;
+    if (!aligned16(L->W_packed)) return HGF_ERR_ALIGN;
+    return HGF_OK;
+}
+
+hgf_status from_hip(hipError_t e) { return e == hipSuccess ? HGF_OK : HGF_ERR_DEVICE; }
+
+// Steps 1-2 and 5-6 for one input (shared by layers reading the same slot), then the
+// main kernel per layer.
+hgf_status run_layer(const void *x, int M, const hgf_layer &L, void *y, int32_t *acc_debug, const Workspace &ws,
+                     bool quantise, hipStream_t st)
+{
+    const _Float16 *xh = reinterpret_cast<const _Float16 *>(x);
+    if (quantise) {
+        hipError_t e = launch_quantize(xh, M, L.d_in, ws.xq, ws.s_x, ws.rowsum, st);
+        if (e != hipSuccess) return HGF_ERR_DEVICE;
+    }
+    if (L.rank > 0) {
+        hipError_t e = launch_corr_down(xh, M, L.d_in, reinterpret_cast<const _Float16 *>(L.A_f16), L.rank, ws, st);
+        if (e != hipSuccess) return HGF_ERR_DEVICE;
+    }
+    hipError_t e = (M <= kMaxDecodeM) ? launch_decode(ws, M, L, reinterpret_cast<_Float16 *>(y), acc_debug, st)
+                                      : launch_prefill(ws, M, L, reinterpret_cast<_Float16 *>(y), acc_debug, st);
+    return from_hip(e);
+}
+
+}  // namespace
+}  // namespace hgf
+
+using namespace hgf;
+
+extern "C" {
+
+const char *hgf_status_string(int status)
+{
+    switch (status) {
+        case HGF_OK: return "HGF_OK";
+        case HGF_ERR_NULL: return "HGF_ERR_NULL: a required pointer is NULL";
+        case HGF_ERR_SHAPE: return "HGF_ERR_SHAPE: a dimension is out of range";
+        case HGF_ERR_ALIGN: return "HGF_ERR_ALIGN: a buffer is not 16-byte aligned";
+        case HGF_ERR_UNSUPPORTED: return "HGF_ERR_UNSUPPORTED";
+        case HGF_ERR_WORKSPACE: return "HGF_ERR_WORKSPACE: workspace missing or too small";
+        case HGF_ERR_DEVICE: return "HGF_ERR_DEVICE: the HIP runtime refused a launch";
+        default: return "HGF: unknown status";
+    }
+}
+
+int hgf_version(void) { return 100; }
+
+int hgf_padded_k(int d_in) { return (d_in >= 1 && d_in <= HGF_MAX_DIM) ? round_up(d_in, kTile) : 0; }
+
+size_t hgf_packed_weight_bytes(int d_out, int d_in)
+{
+    if (!dims_ok(d_in, d_out)) return 0;
+    return (size_t)(round_up(d_out, kTile) / kTile) * (round_up(d_in, kTile) / kTile) * kTileBytes;
+}
+
+size_t hgf_workspace_bytes(int M_max, int d_in_max, int d_out_max, int rank_max)
+{
+    if (!dims_ok(d_in_max, d_out_max) || rank_max < 0 || rank_max > HGF_MAX_RANK) return 0;
+    if (!tokens_ok(M_max, d_in_max, d_out_max)) return 0;
+    return carve_workspace(nullptr, M_max, d_in_max, d_out_max, rank_max).bytes;
+}
+
+hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return HGF_ERR_NULL;
+    if (!aligned16(workspace)) return HGF_ERR_ALIGN;
+    if (workspace_bytes < align256(kAccZeroBytes) + align256(size_t(kNumCounters) * 4)) return HGF_ERR_WORKSPACE;
+    return from_hip(launch_fill_zero(workspace, align256(kAccZeroBytes) + align256(size_t(kNumCounters) * 4),
+                                     reinterpret_cast<hipStream_t>(stream)));
+}
+
+hgf_status hgf_quantize_pack_weights(const float *W, int d_out, int d_in, void *packed_out, float *s_w_out,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!W || !packed_out || !s_w_out) return HGF_ERR_NULL;
+    if (!dims_ok(d_in, d_out)) return HGF_ERR_SHAPE;
+    if (!aligned16(packed_out)) return HGF_ERR_ALIGN;
+    if (!workspace) return HGF_ERR_WORKSPACE;
+    const Workspace ws = carve_workspace(workspace, 1, 1, 1, 0);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (launch_wsum(W, (size_t)d_out * d_in, ws.wsum, s_w_out, st) != hipSuccess) return HGF_ERR_DEVICE;
+    return from_hip(launch_pack(W, d_out, d_in, s_w_out, reinterpret_cast<uint32_t *>(packed_out), st));
+}
+
+hgf_status hgf_unpack_weights(const void *packed, int d_out, int d_in, int8_t *T_out, void *stream)
+{
+    if (!packed || !T_out) return HGF_ERR_NULL;
+    if (!dims_ok(d_in, d_out)) return HGF_ERR_SHAPE;
+    if (!aligned16(packed)) return HGF_ERR_ALIGN;
+    return from_hip(launch_unpack(reinterpret_cast<const uint32_t *>(packed), d_out, d_in, T_out,
+                                  reinterpret_cast<hipStream_t>(stream)));
+}
+
+hgf_status hgf_quantize_activations(const void *x_f16, int M, int d_in, int8_t *xq_out, float *s_x_out,
+                                    int32_t *rowsum_out, void *stream)
+{
+    if (!x_f16 || !xq_out || !s_x_out) return HGF_ERR_NULL;
+    if (!dims_ok(d_in, 1) || !tokens_ok(M, d_in, 1)) return HGF_ERR_SHAPE;
+    if (!aligned16(x_f16) || !aligned16(xq_out)) return HGF_ERR_ALIGN;
+    return from_hip(launch_quantize(reinterpret_cast<const _Float16 *>(x_f16), M, d_in, xq_out, s_x_out, rowsum_out,
+                                    reinterpret_cast<hipStream_t>(stream)));
+}
+
+hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void *y_f16, int32_t *acc_debug,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x_f16 || !y_f16) return HGF_ERR_NULL;
+    const hgf_status s = check_layer(L, M);
+    if (s != HGF_OK) return s;
+    if (!aligned16(x_f16) || !aligned16(y_f16) || (acc_debug && !aligned16(acc_debug))) return HGF_ERR_ALIGN;
+    if (!workspace) return HGF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return HGF_ERR_ALIGN;
+    const Workspace ws = carve_workspace(workspace, M, L->d_in, L->d_out, L->rank);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    return run_layer(x_f16, M, *L, y_f16, acc_debug, ws, true, reinterpret_cast<hipStream_t>(stream));
+}
+
+hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const *slots, int n_slots, int M,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!layers || !slots) return HGF_ERR_NULL;
+    if (n_layers < 1 || n_slots < 1) return HGF_ERR_SHAPE;
+    int d_in_max = 1, d_out_max = 1, rank_max = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        const hgf_layer &L = layers[i];
+        const hgf_status s = check_layer(&L, M);
+        if (s != HGF_OK) return s;
+        if (L.src_slot < 0 || L.src_slot >= n_slots || L.dst_slot < 0 || L.dst_slot >= n_slots ||
+            L.src_slot == L.dst_slot)
+            return HGF_ERR_SHAPE;
+        if (!slots[L.src_slot] || !slots[L.dst_slot]) return HGF_ERR_NULL;
+        if (!aligned16(slots[L.src_slot]) || !aligned16(slots[L.dst_slot])) return HGF_ERR_ALIGN;
+        if (L.d_in > d_in_max) d_in_max = L.d_in;
+        if (L.d_out > d_out_max) d_out_max = L.d_out;
+        if (L.rank > rank_max) rank_max = L.rank;
+    }
+    if (!workspace) return HGF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return HGF_ERR_ALIGN;
+    const Workspace ws = carve_workspace(workspace, M, d_in_max, d_out_max, rank_max);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    for (int i = 0; i < n_layers; ++i) {
+        const hgf_layer &L = layers[i];
+        // the quantised input is reused while consecutive layers read the same slot and
+        // no layer in between has overwritten it
+        bool quantise = true;
+        if (i > 0 && layers[i - 1].src_slot == L.src_slot && layers[i - 1].d_in == L.d_in &&
+            layers[i - 1].dst_slot != L.src_slot)
+            quantise = false;
+        const hgf_status s = run_layer(slots[L.src_slot], M, L, slots[L.dst_slot], nullptr, ws, quantise, st);
+        if (s != HGF_OK) return s;
+    }
+    return HGF_OK;
+}
+
+/* Tuning hook for benchmarks: target number of decode workgroups per launch (0 = default). */
+void hgf_set_decode_target_workgroups(int n) { set_decode_target_wgs(n); }
+
+}  // extern "C"

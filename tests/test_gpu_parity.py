@@ -1,0 +1,205 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element
+on the same seeded inputs.  Integers (codes, x_q, rowsum, int32 accumulators) and the fp32
+scales bit-exact; fp16 outputs within 2e-3 + 1e-2 |y|."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hgf_oracle as orc
+from paper_2602_05269_amd import binding as hb
+from paper_2602_05269_amd import synth
+from parity import GpuLayer, assert_close_fp16, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ws():
+    return hb.Workspace(2048, 11008, 11008, 128)
+
+
+# ------------------------------------------------------------------ quantiser
+
+@pytest.mark.parametrize("M,K,kind", [(1, 1, "normal"), (3, 63, "normal"), (8, 256, "normal"), (5, 1365, "student_t3"),
+                                      (16, 2048, "outlier"), (7, 11008, "student_t3"), (300, 3072, "student_t4")])
+def test_quantize_activations_bit_exact(M, K, kind):
+    x = synth.draw_activations(kind, np.random.default_rng([M, K]), M, K)
+    if M >= 3:
+        x[1] = 0                                       # an all-zero token
+        x[2, K // 2] = np.float16(60000.0)             # a huge outlier
+    xq, s_x, rowsum = hb.hgf_quantize_activations(dev(x))
+    torch.cuda.synchronize()
+    xq_ref, s_ref, rs_ref = orc.quantize_act(x)
+    xq = xq.cpu().numpy()
+    assert np.array_equal(xq[:, :K], xq_ref)
+    assert not xq[:, K:].any()                         # padding columns are zero
+    assert np.array_equal(s_x.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(rowsum.cpu().numpy(), rs_ref)
+
+
+# ------------------------------------------------------------------ weights
+
+@pytest.mark.parametrize("N,K", [(1, 1), (3, 63), (64, 64), (65, 65), (100, 1365), (256, 256), (2048, 512)])
+def test_pack_unpack_matches_oracle_ternariser(N, K, ws):
+    c = synth.make_custom(N * 7 + K, 1, K, N, 8)
+    g = GpuLayer(c, ws)
+    g.check_weights()
+
+
+def test_pack_constructed_ties_and_zero_matrix(ws):
+    W = np.array([[0.5, -0.5, 1.5, -1.5], [0.25, -0.25, 1.75, -1.75]], dtype=np.float32)
+    packed, s_w = hb.hgf_quantize_pack_weights(dev(W), ws)
+    T = hb.hgf_unpack_weights(packed, 2, 4).cpu().numpy()
+    assert s_w.item() == 1.0 and T.tolist() == [[0, 0, 1, -1], [0, 0, 1, -1]]
+    packed, s_w = hb.hgf_quantize_pack_weights(dev(np.zeros((5, 70), dtype=np.float32)), ws)
+    assert s_w.cpu().numpy()[0] == np.float32(1e-5)
+    assert not hb.hgf_unpack_weights(packed, 5, 70).cpu().numpy().any()
+    # padding codes decode to zero: every 2-bit field of the buffer is 0, 1 or 2, padding is 1
+    raw = packed.cpu().numpy()
+    fields = np.stack([(raw >> s) & 3 for s in (0, 2, 4, 6)])
+    assert (fields == 1).all()
+
+
+# ------------------------------------------------------------------ one layer
+
+def test_config0_full_parity(ws):
+    w = synth.make_weights(0, 0, 0)
+    g = GpuLayer(w, ws)
+    g.check_weights()
+    x = synth.make_activations(0, 0, 0, 8)
+    g.check_forward(x)
+
+
+@pytest.mark.parametrize("M,K,N,r", [
+    (1, 64, 64, 16), (1, 512, 512, 32), (2, 100, 37, 8), (4, 1365, 130, 32), (8, 256, 192, 1),
+    (16, 2048, 256, 64), (17, 320, 257, 24), (33, 1000, 66, 128), (48, 4096, 128, 48), (64, 704, 320, 128),
+    (1, 11008, 256, 128), (5, 63, 1, 5),
+])
+def test_decode_shapes_parity(M, K, N, r, ws):
+    c = synth.make_custom(1000 + M + K + N + r, M, K, N, r, act="student_t3")
+    g = GpuLayer(c, ws)
+    g.check_forward(c["x"])
+
+
+@pytest.mark.parametrize("M,K,N,r", [(65, 256, 128, 16), (130, 512, 200, 32), (256, 1365, 256, 64)])
+def test_large_m_parity(M, K, N, r, ws):
+    c = synth.make_custom(2000 + M + K + N + r, M, K, N, r, act="student_t4")
+    g = GpuLayer(c, ws)
+    g.check_forward(c["x"])
+
+
+def test_gate_off_and_rank0_are_the_pure_ternary_layer(ws):
+    c = synth.make_custom(77, 8, 512, 256, 32)
+    full = GpuLayer(c, ws)
+    y_full, ref = full.check_forward(c["x"])
+    c_off = dict(c, alpha=np.zeros_like(c["alpha"]))
+    y_off, _ = GpuLayer(c_off, ws).check_forward(c["x"])
+    y_r0, _ = GpuLayer(c, ws, rank0=True).check_forward(c["x"])
+    assert np.array_equal(y_off, y_r0)
+    assert_close_fp16(y_r0, ref["y_tern"])
+    assert not np.array_equal(y_full, y_r0)
+
+
+def test_zero_token_and_extreme_accumulators(ws):
+    K, N = 11008, 128
+    W = np.full((N, K), 0.02, dtype=np.float32)
+    W[1::2] *= -1                                       # rows alternate all +1 / all -1
+    c = {"W": W, "d_in": K, "d_out": N, "rank": 0}
+    g = GpuLayer(c, ws, rank0=True)
+    x = np.full((3, K), 2.0, dtype=np.float16)
+    x[1] = 0
+    y, acc = g.forward(x)
+    assert acc[0, 0] == 127 * K and acc[0, 1] == -127 * K and not acc[1].any() and not y[1].any()
+    g.check_forward(x)
+
+
+def test_repeated_calls_reuse_the_workspace(ws):
+    """Split-K scratch and counters are left clean: the same call twice, then a different
+    shape, all on one workspace, give the oracle's integers every time."""
+    a = synth.make_custom(5, 1, 4096, 512, 64)
+    b = synth.make_custom(6, 16, 2048, 1024, 32)
+    ga, gb = GpuLayer(a, ws), GpuLayer(b, ws)
+    for _ in range(3):
+        ga.check_forward(a["x"])
+        gb.check_forward(b["x"])
+
+
+# ------------------------------------------------------------------ stack
+
+def _stack_case(cfg, M, ws, n_layers=None):
+    c = synth.CONFIGS[cfg]
+    wiring = synth.stack_wiring(cfg)
+    if n_layers is not None:
+        wiring = [w for w in wiring if w[0] < n_layers]
+    cases, layers = [], []
+    n_slots = 1 + max(w[3] for w in wiring)
+    slots = [None] * n_slots
+    x0 = synth.make_activations(cfg, 0, 0, M)
+    slots[0] = dev(x0)
+    for (layer, proj, src, dst) in wiring:
+        w = synth.make_weights(cfg, layer, proj)
+        g = GpuLayer(w, ws)
+        g.layer.c.src_slot, g.layer.c.dst_slot = src, dst
+        cases.append(g)
+        layers.append(g.layer)
+        slots[dst] = torch.zeros((M, w["d_out"]), dtype=torch.float16, device="cuda")
+    return cases, layers, slots, wiring, x0
+
+
+def test_config1_stack_teacher_forced(ws):
+    """The 8-layer, 56-linear decode stack at M=1 through hgf_stack_forward.  Every linear is
+    checked against the oracle on the input the GPU actually gave it (the slot it read), so
+    each of the 56 outputs meets the single-layer bar; the end of the chain is also compared
+    with the oracle's own chain."""
+    cases, layers, slots, wiring, x0 = _stack_case(1, 1, ws)
+    st = hb.Stack(layers, slots, 1)
+    hb.hgf_stack_forward(st, ws)
+    torch.cuda.synchronize()
+    host = [s.cpu().numpy() for s in slots]
+    for g, (_, _, src, dst) in zip(cases, wiring):
+        ref = g.oracle(host[src])
+        assert_close_fp16(host[dst], ref["y"], f"slot {dst}")
+        # the single-layer entry point gives the same bits as the stack did
+        y1, acc1 = g.forward(host[src])
+        assert np.array_equal(y1, host[dst])
+        assert np.array_equal(acc1, ref["acc"])
+    chain = orc.stack_forward([{"T": g.T_ref, "s_w": g.s_w_ref, "A": g.case["A"], "B": g.case["B"],
+                                "alpha": g.case["alpha"]} for g in cases], [(w[2], w[3]) for w in wiring], x0)
+    end = wiring[-1][3]
+    ref_end = chain[end].astype(np.float64)
+    rel = np.linalg.norm(host[end].astype(np.float64) - ref_end) / np.linalg.norm(ref_end)
+    assert rel < 0.05, rel
+
+
+# ------------------------------------------------------------------ full-size configurations, sampled
+
+def _sampled(cfg, proj, M, ws, n_rows=96, n_tok=None):
+    w = synth.make_weights(cfg, 0, proj)
+    g = GpuLayer(w, ws)
+    x = synth.make_activations(cfg, 0, proj, M)
+    rng = np.random.default_rng(cfg * 100 + proj)
+    rows = np.sort(rng.choice(w["d_out"], size=n_rows, replace=False))
+    rows[0], rows[-1] = 0, w["d_out"] - 1
+    tokens = None
+    if n_tok is not None and n_tok < M:
+        tokens = np.sort(rng.choice(M, size=n_tok, replace=False))
+        tokens[0], tokens[-1] = 0, M - 1
+    T = hb.hgf_unpack_weights(g.layer.packed, g.N, g.K).cpu().numpy()
+    assert np.array_equal(T, g.T_ref)
+    g.check_forward(x, rows=rows, tokens=tokens)
+
+
+@pytest.mark.parametrize("proj", [0, 4, 6])
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_config2_sampled(proj, M, ws):
+    _sampled(2, proj, M, ws)
+
+
+@pytest.mark.parametrize("proj,M", [(0, 1), (0, 64), (1, 8), (2, 1), (2, 32), (2, 64)])
+def test_config4_sampled(proj, M, ws):
+    _sampled(4, proj, M, ws)
+
+
+@pytest.mark.parametrize("proj", [0, 4, 6])
+def test_config3_prefill_sampled(proj, ws):
+    _sampled(3, proj, 2048, ws, n_rows=48, n_tok=24)
