@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
     L.hgf_stack_forward.argtypes = [ctypes.POINTER(hgf_layer), ci, ctypes.POINTER(vp), ci, ci, vp, sz, vp]
     L.hgf_set_decode_target_workgroups.restype = None
     L.hgf_set_decode_target_workgroups.argtypes = [ci]
+    L.hgf_profile_enable.restype = None
+    L.hgf_profile_enable.argtypes = [ci]
+    L.hgf_profile_collect.restype = ci
+    L.hgf_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_longlong)]
     _lib = L
     return L
 
@@ -127,6 +131,18 @@ def hgf_workspace_init(ws: Workspace, stream=None) -> None:
 
 def hgf_set_decode_target_workgroups(n: int) -> None:
     lib().hgf_set_decode_target_workgroups(n)
+
+
+def hgf_profile_enable(on: bool) -> None:
+    lib().hgf_profile_enable(1 if on else 0)
+
+
+def hgf_profile_collect():
+    """((decode_ms, decode_launches), (prefill_ms, prefill_launches)) since the last collect."""
+    ms = (ctypes.c_double * 2)()
+    n = (ctypes.c_longlong * 2)()
+    _check(lib().hgf_profile_collect(ms, n), "hgf_profile_collect")
+    return (ms[0], n[0]), (ms[1], n[1])
 
 
 # --------------------------------------------------------------------------- steps

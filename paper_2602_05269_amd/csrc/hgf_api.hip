@@ -2,6 +2,9 @@
 // Every check happens before the first HIP call, so the error paths run without a GPU.
 #include "hgf_internal.h"
 
+#include <utility>
+#include <vector>
+
 namespace hgf {
 
 Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
@@ -16,7 +19,7 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     };
     ws.acc = reinterpret_cast<int32_t *>(take(kAccZeroBytes));
     ws.counters = reinterpret_cast<int32_t *>(take(size_t(kNumCounters) * 4));
-    const int Kp = round_up(d_in, kTile);
+    const int Kp = round_up(d_in, kTileCols);
     ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
     ws.rowsum = reinterpret_cast<int32_t *>(take((size_t)M * 4));
@@ -25,6 +28,9 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     // rank (the launcher uses at most min(32, ceil(768/tiles)) slices over `tiles` token tiles)
     const size_t hpart = rank > 0 ? (size_t)(768 + (M + 15) / 16) * h_rank_tiles(rank) * 64 * 16 : 0;
     ws.hpart = reinterpret_cast<float *>(take(hpart));
+    // decode: per layer of a group at most 64 (slice, token) rows of h_stride partial sums
+    ws.hslices_each = rank > 0 ? align256((size_t)64 * h_stride(rank) * sizeof(float)) : 0;
+    ws.hslices = reinterpret_cast<float *>(take(ws.hslices_each * kMaxGroup));
     ws.wsum = reinterpret_cast<double *>(take(size_t(kWsumBlocks) * 8));
     (void)d_out;
     ws.bytes = off;
@@ -55,23 +61,127 @@ hgf_status check_layer(const hgf_layer *L, int M)
 
 hgf_status from_hip(hipError_t e) { return e == hipSuccess ? HGF_OK : HGF_ERR_DEVICE; }
 
-// Steps 1-2 and 5-6 for one input (shared by layers reading the same slot), then the
-// main kernel per layer.
-hgf_status run_layer(const void *x, int M, const hgf_layer &L, void *y, int32_t *acc_debug, const Workspace &ws,
-                     bool quantise, hipStream_t st)
+// Profiling aid: event pairs recorded around main-kernel launches, by kind (0 decode, 1 prefill).
+bool g_profile = false;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events[2];
+std::vector<hipEvent_t> g_event_pool;
+
+hipEvent_t take_event()
+{
+    hipEvent_t e = nullptr;
+    if (!g_event_pool.empty()) {
+        e = g_event_pool.back();
+        g_event_pool.pop_back();
+    } else if (hipEventCreate(&e) != hipSuccess) {
+        e = nullptr;
+    }
+    return e;
+}
+
+// Records an event pair around a main-kernel launch when profiling is on.
+struct ProfileScope {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipStream_t st;
+    int kind;
+    ProfileScope(int kind_, hipStream_t st_) : st(st_), kind(kind_)
+    {
+        if (!g_profile) return;
+        e0 = take_event();
+        e1 = take_event();
+        if (e0 && e1) (void)hipEventRecord(e0, st);
+    }
+    ~ProfileScope()
+    {
+        if (e0 && e1) {
+            (void)hipEventRecord(e1, st);
+            g_events[kind].emplace_back(e0, e1);
+        }
+    }
+};
+
+// Decode (M <= 64): `G` layers that read the same activations `x` run as two launches:
+// the fused prologue (quantiser + partial sums of every A x) and one grouped main kernel.
+hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
+                            int32_t *acc_debug, const Workspace &ws, hipStream_t st)
+{
+    const int K = layers[0].d_in;
+    ProParams pp;
+    pp.x = reinterpret_cast<const _Float16 *>(x);
+    pp.xq = ws.xq;
+    pp.s_x = ws.s_x;
+    pp.rowsum = ws.rowsum;
+    pp.M = M;
+    pp.K = K;
+    pp.Kp = round_up(K, kTileCols);
+    pp.G = G;
+    DecodeParams dp;
+    dp.xq = ws.xq;
+    dp.s_x = ws.s_x;
+    dp.rowsum = ws.rowsum;
+    dp.M = M;
+    dp.G = G;
+    dp.hmode = 0;
+    for (int g = 0; g < G; ++g) {
+        const hgf_layer &L = layers[g];
+        float *slices = reinterpret_cast<float *>(reinterpret_cast<char *>(ws.hslices) + ws.hslices_each * g);
+        pp.L[g].A = reinterpret_cast<const _Float16 *>(L.A_f16);
+        pp.L[g].hpart = slices;
+        pp.L[g].rank = L.rank;
+        pp.L[g].rp = h_stride(L.rank > 0 ? L.rank : 1);
+        DecLayer &D = dp.L[g];
+        D.packed = reinterpret_cast<const v4u *>(L.W_packed);
+        D.s_w = L.s_w;
+        D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
+        D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
+        D.hpart = slices;
+        D.h16 = nullptr;
+        D.y = reinterpret_cast<_Float16 *>(ys[g]);
+        D.acc_debug = acc_debug;
+        D.N = L.d_out;
+        D.RBn = round_up(L.d_out, kTileRows) / kTileRows;
+        D.rank = L.rank;
+        D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
+    }
+    if (launch_prologue(pp, st) != hipSuccess) return HGF_ERR_DEVICE;
+    dp.S = pp.S;
+    ProfileScope prof(0, st);
+    return from_hip(launch_decode(dp, K, st));
+}
+
+// Large M: per layer, quantiser (shared by the group), split down-projection with SiLU,
+// then the main kernel in columns of 64 tokens.
+hgf_status run_large_layer(const void *x, int M, const hgf_layer &L, void *y, int32_t *acc_debug,
+                           const Workspace &ws, bool quantise, hipStream_t st)
 {
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(x);
-    if (quantise) {
-        hipError_t e = launch_quantize(xh, M, L.d_in, ws.xq, ws.s_x, ws.rowsum, st);
-        if (e != hipSuccess) return HGF_ERR_DEVICE;
-    }
-    if (L.rank > 0) {
-        hipError_t e = launch_corr_down(xh, M, L.d_in, reinterpret_cast<const _Float16 *>(L.A_f16), L.rank, ws, st);
-        if (e != hipSuccess) return HGF_ERR_DEVICE;
-    }
-    hipError_t e = (M <= kMaxDecodeM) ? launch_decode(ws, M, L, reinterpret_cast<_Float16 *>(y), acc_debug, st)
-                                      : launch_prefill(ws, M, L, reinterpret_cast<_Float16 *>(y), acc_debug, st);
-    return from_hip(e);
+    if (quantise && launch_quantize(xh, M, L.d_in, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess)
+        return HGF_ERR_DEVICE;
+    if (L.rank > 0 &&
+        launch_corr_down(xh, M, L.d_in, reinterpret_cast<const _Float16 *>(L.A_f16), L.rank, ws, st) != hipSuccess)
+        return HGF_ERR_DEVICE;
+    DecodeParams dp;
+    dp.xq = ws.xq;
+    dp.s_x = ws.s_x;
+    dp.rowsum = ws.rowsum;
+    dp.M = M;
+    dp.G = 1;
+    dp.hmode = 1;
+    dp.S = 1;
+    DecLayer &D = dp.L[0];
+    D.packed = reinterpret_cast<const v4u *>(L.W_packed);
+    D.s_w = L.s_w;
+    D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
+    D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
+    D.hpart = nullptr;
+    D.h16 = ws.h16;
+    D.y = reinterpret_cast<_Float16 *>(y);
+    D.acc_debug = acc_debug;
+    D.N = L.d_out;
+    D.RBn = round_up(L.d_out, kTileRows) / kTileRows;
+    D.rank = L.rank;
+    D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
+    ProfileScope prof(1, st);
+    return from_hip(launch_decode(dp, L.d_in, st));
 }
 
 }  // namespace
@@ -97,12 +207,12 @@ const char *hgf_status_string(int status)
 
 int hgf_version(void) { return 100; }
 
-int hgf_padded_k(int d_in) { return (d_in >= 1 && d_in <= HGF_MAX_DIM) ? round_up(d_in, kTile) : 0; }
+int hgf_padded_k(int d_in) { return (d_in >= 1 && d_in <= HGF_MAX_DIM) ? round_up(d_in, kTileCols) : 0; }
 
 size_t hgf_packed_weight_bytes(int d_out, int d_in)
 {
     if (!dims_ok(d_in, d_out)) return 0;
-    return (size_t)(round_up(d_out, kTile) / kTile) * (round_up(d_in, kTile) / kTile) * kTileBytes;
+    return (size_t)(round_up(d_out, kTileRows) / kTileRows) * (round_up(d_in, kTileCols) / kTileCols) * kTileBytes;
 }
 
 size_t hgf_workspace_bytes(int M_max, int d_in_max, int d_out_max, int rank_max)
@@ -165,7 +275,12 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
     if (!aligned16(workspace)) return HGF_ERR_ALIGN;
     const Workspace ws = carve_workspace(workspace, M, L->d_in, L->d_out, L->rank);
     if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
-    return run_layer(x_f16, M, *L, y_f16, acc_debug, ws, true, reinterpret_cast<hipStream_t>(stream));
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (M <= kMaxDecodeM) {
+        void *ys[1] = {y_f16};
+        return run_decode_group(x_f16, M, L, 1, ys, acc_debug, ws, st);
+    }
+    return run_large_layer(x_f16, M, *L, y_f16, acc_debug, ws, true, st);
 }
 
 hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const *slots, int n_slots, int M,
@@ -192,16 +307,56 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
     const Workspace ws = carve_workspace(workspace, M, d_in_max, d_out_max, rank_max);
     if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    for (int i = 0; i < n_layers; ++i) {
-        const hgf_layer &L = layers[i];
-        // the quantised input is reused while consecutive layers read the same slot and
-        // no layer in between has overwritten it
-        bool quantise = true;
-        if (i > 0 && layers[i - 1].src_slot == L.src_slot && layers[i - 1].d_in == L.d_in &&
-            layers[i - 1].dst_slot != L.src_slot)
-            quantise = false;
-        const hgf_status s = run_layer(slots[L.src_slot], M, L, slots[L.dst_slot], nullptr, ws, quantise, st);
-        if (s != HGF_OK) return s;
+    int i = 0;
+    while (i < n_layers) {
+        // a group: consecutive layers reading the same slot with the same d_in, none of which
+        // writes that slot or a slot another member writes
+        int G = 1;
+        while (i + G < n_layers && G < kMaxGroup) {
+            const hgf_layer &C = layers[i + G];
+            bool ok = C.src_slot == layers[i].src_slot && C.d_in == layers[i].d_in;
+            for (int j = i; ok && j < i + G; ++j) ok = layers[j].dst_slot != C.dst_slot;
+            if (!ok) break;
+            ++G;
+        }
+        const void *x = slots[layers[i].src_slot];
+        if (M <= kMaxDecodeM) {
+            void *ys[kMaxGroup];
+            for (int g = 0; g < G; ++g) ys[g] = slots[layers[i + g].dst_slot];
+            const hgf_status s = run_decode_group(x, M, layers + i, G, ys, nullptr, ws, st);
+            if (s != HGF_OK) return s;
+        } else {
+            for (int g = 0; g < G; ++g) {
+                const hgf_status s = run_large_layer(x, M, layers[i + g], slots[layers[i + g].dst_slot], nullptr, ws,
+                                                     g == 0, st);
+                if (s != HGF_OK) return s;
+            }
+        }
+        i += G;
+    }
+    return HGF_OK;
+}
+
+void hgf_profile_enable(int on) { g_profile = on != 0; }
+
+hgf_status hgf_profile_collect(double *ms_out, long long *launches_out)
+{
+    if (!ms_out || !launches_out) return HGF_ERR_NULL;
+    for (int kind = 0; kind < 2; ++kind) {
+        double total = 0.0;
+        long long n = 0;
+        for (auto &pr : g_events[kind]) {
+            float ms = 0.f;
+            if (hipEventSynchronize(pr.second) == hipSuccess && hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+                total += ms;
+                ++n;
+            }
+            g_event_pool.push_back(pr.first);
+            g_event_pool.push_back(pr.second);
+        }
+        g_events[kind].clear();
+        ms_out[kind] = total;
+        launches_out[kind] = n;
     }
     return HGF_OK;
 }

@@ -69,25 +69,32 @@ __global__ __launch_bounds__(64) void corr_down_kernel(CorrParams p)
 
     // acc[rt][v] holds rank index rt*16 + 4*(l/16) + v for token tt*16 + (l%16)
     if (p.splits > 1) {
+        // Partial sums cross workgroups (and XCDs, whose L2 caches are not coherent with each
+        // other) as device-scope atomic stores and loads, which go to the point of coherence:
+        // no cache write-back or invalidate.  The arrival counter moves once they are acknowledged.
         const int ntt = gridDim.x / p.splits;
-        v4f *mine = reinterpret_cast<v4f *>(p.hpart) + ((size_t)(sp * ntt + tt) * RTN) * 64;
+        float *mine = p.hpart + ((size_t)(sp * ntt + tt) * RTN) * 256;
 #pragma unroll
-        for (int rt = 0; rt < RTN; ++rt) mine[rt * 64 + l] = acc[rt];
-        __threadfence();
+        for (int rt = 0; rt < RTN; ++rt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                __hip_atomic_store(&mine[(rt * 4 + v) * 64 + l], acc[rt][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
         int old = 0;
-        if (l == 0) old = atomicAdd(&p.counters[tt], 1);
+        if (l == 0) old = __hip_atomic_fetch_add(&p.counters[tt], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         old = __shfl(old, 0, 64);
         if (old != p.splits - 1) return;
-        if (l == 0) atomicExch(&p.counters[tt], 0);
-        __threadfence();
+        if (l == 0) __hip_atomic_exchange(&p.counters[tt], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int rt = 0; rt < RTN; ++rt) acc[rt] = (v4f){0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < p.splits; ++s) {
-            const v4f *part = reinterpret_cast<const v4f *>(p.hpart) + ((size_t)(s * ntt + tt) * RTN) * 64;
+            const float *part = p.hpart + ((size_t)(s * ntt + tt) * RTN) * 256;
 #pragma unroll
-            for (int rt = 0; rt < RTN; ++rt) {
-                acc[rt] += part[rt * 64 + l];
-            }
+            for (int rt = 0; rt < RTN; ++rt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    acc[rt][v] += __hip_atomic_load(&part[(rt * 4 + v) * 64 + l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 

@@ -1,47 +1,27 @@
-// Decode kernel (M <= 64 per launch column): packed ternary weights x int8 activations,
-// fused with dequantisation, the rank-r up-projection and the gate.
+// Decode kernel (up to 64 tokens per launch column): packed ternary weights x int8
+// activations, fused with dequantisation, the rank-r up-projection and the gate.
 //
 // Algorithm 1 of the HGF paper, steps 3, 4, 7 and 8:
 //   acc[m,n] = sum_k T[n,k] x_q[m,k]                       (exact int32)
 //   y[m,n]   = acc * (s_x[m] s_w) + tanh(alpha[n]) * sum_j B[n,j] h[m,j]
-// The weights are streamed from HBM exactly once with 16-byte loads per lane (1 KiB per
-// wavefront instruction, one 64x64 tile); the 2-bit codes are widened to int8 in
-// registers (a shift and a mask per four codes) and contracted on the 16x16x64 int8 MFMA
-// with the 16 weight rows as matrix rows and up to 16 tokens as matrix columns.  Codes are
-// T+1, so the MFMA accumulates sum (T+1) x_q and the per-token sum of x_q is subtracted
-// once at the end: integer-exact, no per-weight subtract.
+// The weights are streamed from HBM exactly once with 16-byte loads per lane: one
+// wavefront instruction fetches one 1 KiB tile (16 rows x 256 columns).  The 2-bit codes
+// are widened to int8 in registers (a shift and a mask per four codes) and contracted on
+// the 16x16x64 int8 MFMA with the 16 weight rows as matrix rows and up to 16 tokens as
+// matrix columns.  Codes are T+1, so the MFMA accumulates sum (T+1) x_q and the per-token
+// sum of x_q is subtracted once at the end: integer-exact, no per-weight subtract.
 //
-// Work split: one workgroup of four wavefronts per (row-block of 64 rows, slice of d_in);
-// the wavefronts take the slice's tiles round-robin and add their partial tiles through
-// LDS.  With more than one slice per row-block the partial sums are added into a zeroed
-// int32 scratch with device-scope atomics (integer addition: order does not matter) and
-// the last workgroup to arrive for the row-block swaps them back out (leaving zeros) and
-// runs the epilogue.
+// Work split: a workgroup of four wavefronts covers RW row-blocks of 16 rows, with KW =
+// 4/RW wavefronts sharing each row-block's tiles round-robin along d_in and adding their
+// partial tiles through LDS.  The quantised activations of the current stretch of d_in
+// sit in LDS, shared by the four wavefronts; only lanes whose token exists read them.
+// Every wavefront issues all weight loads of a batch before it consumes the first, so a
+// compute unit keeps tens of KiB in flight.  Nothing crosses workgroups: no atomics.
 #include "hgf_internal.h"
 
 namespace hgf {
 
 namespace {
-
-struct DecodeParams {
-    const v4u *packed;
-    const int8_t *xq;
-    const float *s_x;
-    const int32_t *rowsum;
-    const float *s_w;
-    const _Float16 *B;
-    const _Float16 *alpha;
-    const _Float16 *h16;
-    _Float16 *y;
-    int32_t *acc_debug;
-    int32_t *acc_ws;
-    int32_t *counters;
-    int M, N, Np, Kp, KS;
-    int rank, hstride;
-    int splits, ks_per_split;
-};
-
-template <int TT> struct ChunkOf { static constexpr int value = TT == 1 ? 32 : (TT == 2 ? 16 : 8); };
 
 __device__ inline v4i widen_codes(uint32_t w)
 {
@@ -53,209 +33,277 @@ __device__ inline v4i widen_codes(uint32_t w)
     return a;
 }
 
+__device__ inline float silu(float h) { return h / (1.0f + expf(-h)); }
+
 template <int TT>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p)
 {
-    constexpr int CH = ChunkOf<TT>::value;         // k-steps staged in LDS at a time
-    constexpr int ROWS = 16 * TT;                  // token rows staged
-    constexpr int STRIDE = CH * 64 + 16;           // bytes per staged row (+16: bank spread)
-    constexpr int STAGE_BYTES = ROWS * STRIDE;
-    constexpr int RED_BYTES = 4 * 3 * TT * 64 * 16;
-    constexpr int LDS_BYTES = STAGE_BYTES > RED_BYTES ? STAGE_BYTES : RED_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
-    __shared__ int sh_last;
+#ifndef HGF_PF1
+#define HGF_PF1 8
+#endif
+    constexpr int PF = TT == 1 ? HGF_PF1 : (TT == 2 ? 8 : 4);   // weight tiles in flight per wavefront
+    constexpr int XPRE = 4;                                 // activation pieces per thread fetched up front
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-    const int rb = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
-    const int m0 = blockIdx.y * kMaxDecodeM;       // first token of this launch column
-    const int mcount = min(p.M - m0, ROWS);
-    const int ks0 = sp * p.ks_per_split;
-    const int ks1 = min(ks0 + p.ks_per_split, p.KS);
-
-    v4i acc[4][TT];
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // this workgroup's layer: every candidate is read at a fixed kernel-argument offset (one
+    // batch of scalar loads) and selected, instead of a dependent load at a computed offset
+    DecLayer L = p.L[0];
+    int wg0 = 0;
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = (v4i){0, 0, 0, 0};
-
-    const v4u *tiles = p.packed + (size_t)rb * p.KS * 64 + l;   // + ks*64 per tile
-
-    for (int c0 = ks0; c0 < ks1; c0 += CH) {
-        const int nks = min(CH, ks1 - c0);
-        // this wavefront's tiles of the chunk: issue every load before touching LDS
-        v4u wq[CH / 4];
-#pragma unroll
-        for (int t = 0; t < CH / 4; ++t) {
-            const int ks = c0 + w + 4 * t;
-            wq[t] = (v4u){0x55555555u, 0x55555555u, 0x55555555u, 0x55555555u};
-            if (ks < c0 + nks) wq[t] = __builtin_nontemporal_load(&tiles[(size_t)ks * 64]);
+    for (int i = 1; i < kMaxGroup; ++i) {
+        if (i < p.G && (int)blockIdx.x >= p.wg_start[i]) {
+            L = p.L[i];
+            wg0 = p.wg_start[i];
         }
-        __syncthreads();                            // the previous chunk's reads are done
-        const int pieces_per_row = nks * 4;         // 16-byte pieces
-        for (int pc = tid; pc < ROWS * pieces_per_row; pc += 256) {
-            const int row = pc / pieces_per_row, col = pc % pieces_per_row;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row < mcount)
-                v = *reinterpret_cast<const uint4 *>(p.xq + (size_t)(m0 + row) * p.Kp + (size_t)c0 * 64 + col * 16);
-            *reinterpret_cast<uint4 *>(lds + row * STRIDE + col * 16) = v;
-        }
-        __syncthreads();
+    }
+    const int rw = w / p.KW, kw = w % p.KW;
+    const int rb = ((int)blockIdx.x - wg0) * p.RW + rw;   // this wavefront's row-block
+    const bool rb_ok = rb < L.RBn;
+    const int m0 = blockIdx.y * kMaxDecodeM;        // first token of this launch column
+    const int mcount = min(p.M - m0, 16 * TT);
+    const int ml = l & 15, kb = l >> 4;
+    const int n0 = rb * kTileRows;                   // this wavefront's 16 output rows
+    const int nl = n0 + 4 * kb;                      // this lane's 4 consecutive rows
+    const bool owner = rb_ok && kw == 0;             // runs the epilogue of the row-block
+
+    // Loads are issued smallest and most urgent first, the weight stream last, all without
+    // branches, so that everything is in flight together and the small results can be
+    // consumed while the weights are still arriving.
+
+    // ---- (1) partial sums of A x for the first element this thread turns into SiLU(A x)
+    const rsrc_t hr = p.hmode == 0 ? make_rsrc(L.hpart, (unsigned)p.S * p.M * L.hstride * 4u)
+                                   : make_rsrc(L.h16, (unsigned)p.M * L.hstride * 2u);
+    const int htotal = L.rank > 0 ? mcount * L.hstride : 0;
+    float hpre[kMaxHSplit];
+    {
+        const int m = tid / L.hstride, j = tid - m * L.hstride;
+        const bool ok = tid < htotal && j < L.rank;
+        const unsigned row = (unsigned)(m0 + m) * L.hstride + j;
+        if (p.hmode == 0) {
 #pragma unroll
-        for (int t = 0; t < CH / 4; ++t) {
-            const int kl = w + 4 * t;               // k-step within the chunk
-            if (kl < nks) {
-                v4i b[TT];
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    b[tt] = *reinterpret_cast<const v4i *>(lds + (tt * 16 + (l & 15)) * STRIDE + kl * 64 + (l >> 4) * 16);
-#pragma unroll
-                for (int rt = 0; rt < 4; ++rt) {
-                    const v4i a = widen_codes(wq[t][rt]);
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[rt][tt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[tt], acc[rt][tt], 0, 0, 0);
-                }
-            }
+            for (int sp = 0; sp < kMaxHSplit; ++sp)
+                hpre[sp] = __builtin_bit_cast(float, buf_load4(hr, (row + (unsigned)sp * p.M * L.hstride) * 4u,
+                                                               ok && sp < p.S));
+        } else {
+            hpre[0] = (float)half_bits(buf_load2(hr, row * 2u, ok));
         }
     }
 
-    // ---- add the four wavefronts' partial tiles: wavefront w ends up owning row tile w
-    __syncthreads();
+    // ---- (2) the first pieces of the quantised activations (16 bytes each)
+    const int cend0 = min(p.CT, p.KT);
+    const rsrc_t xr = make_rsrc(p.xq + (size_t)m0 * p.Kp, (unsigned)mcount * p.Kp);
+    v4u xpre[XPRE];
     {
+        const int pieces_per_row = cend0 * 16;
+        const int total = mcount * pieces_per_row;
+#pragma unroll
+        for (int u = 0; u < XPRE; ++u) {
+            const int pc = tid + u * 256;
+            const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
+            xpre[u] = buf_load16(xr, (unsigned)row * p.Kp + col * 16, pc < total);
+        }
+    }
+
+    // ---- (3) epilogue operands of the wavefront that owns the row-block
+    constexpr int JS = HGF_MAX_RANK / 32;
+    v8h breg[JS];
+    float alpha_f[4];
+    {
+        const rsrc_t br = make_rsrc(L.B, L.rank > 0 ? (unsigned)L.N * L.rank * 2u : 0u);
+        const rsrc_t ar = make_rsrc(L.alpha, L.rank > 0 ? (unsigned)L.N * 2u : 0u);
+        const int brow = n0 + ml;
+        const bool brow_ok = owner && brow < L.N;
+        const bool bvec = (L.rank % 8) == 0;
+#pragma unroll
+        for (int js = 0; js < JS; ++js) {
+            const int j0 = js * 32 + kb * 8;
+            breg[js] = bvec ? buf_load8h<true>(br, (unsigned)brow * L.rank + j0, L.rank - j0, brow_ok)
+                            : buf_load8h<false>(br, (unsigned)brow * L.rank + j0, L.rank - j0, brow_ok);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) alpha_f[v] = (float)half_bits(buf_load2(ar, (unsigned)(nl + v) * 2u, owner && nl + v < L.N));
+    }
+    const float s_w = *L.s_w;
+    float sx_pre[TT];
+    int rs_pre[TT];
+    {
+        const rsrc_t sr = make_rsrc(p.s_x + m0, (unsigned)mcount * 4u);
+        const rsrc_t rr = make_rsrc(p.rowsum + m0, (unsigned)mcount * 4u);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            sx_pre[tt] = __builtin_bit_cast(float, buf_load4(sr, (unsigned)(tt * 16 + ml) * 4u, owner));
+            rs_pre[tt] = (int)buf_load4(rr, (unsigned)(tt * 16 + ml) * 4u, owner);
+        }
+    }
+
+    // ---- (4) first batch of weight tiles: the bulk of the bytes
+    const v4u *rb_tiles = L.packed + (size_t)(rb_ok ? rb : 0) * p.KT * 64;
+    int kt0 = kw;
+    int cend = cend0;
+    v4u wq[PF];
+    {
+        const rsrc_t wr = make_rsrc(rb_tiles, rb_ok ? (unsigned)cend * kTileBytes : 0u);
+#pragma unroll
+        for (int t = 0; t < PF; ++t) wq[t] = buf_load16_stream(wr, (unsigned)(kt0 + t * p.KW) * kTileBytes + l * 16);
+    }
+
+    // ---- SiLU(A x) of this launch column's tokens into LDS (fp16 rows of hstride)
+    _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off);
+    if (tid < htotal) {
+        float h = hpre[0];
+        if (p.hmode == 0) {
+#pragma unroll
+            for (int sp = 1; sp < kMaxHSplit; ++sp) h += hpre[sp];   // slice order: deterministic
+            h = silu(h);
+        }
+        hs[tid] = (_Float16)h;
+    }
+    for (int idx = tid + 256; idx < htotal; idx += 256) {            // more than 256 elements: M*hstride > 256
+        const int m = idx / L.hstride, j = idx - m * L.hstride;
+        const unsigned row = (unsigned)(m0 + m) * L.hstride + j;
+        float h = 0.f;
+        if (p.hmode == 0) {
+            float part[kMaxHSplit];
+#pragma unroll
+            for (int sp = 0; sp < kMaxHSplit; ++sp)
+                part[sp] = __builtin_bit_cast(float, buf_load4(hr, (row + (unsigned)sp * p.M * L.hstride) * 4u,
+                                                               j < L.rank && sp < p.S));
+#pragma unroll
+            for (int sp = 0; sp < kMaxHSplit; ++sp) h += part[sp];
+            h = silu(h);
+        } else {
+            h = (float)half_bits(buf_load2(hr, row * 2u, j < L.rank));
+        }
+        hs[idx] = (_Float16)h;
+    }
+
+    v4i acc[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) acc[tt] = (v4i){0, 0, 0, 0};
+
+    for (int c0 = 0; c0 < p.KT; c0 += p.CT) {        // stretches of d_in staged in LDS
+        cend = min(c0 + p.CT, p.KT);
+        if (c0 > 0) {
+            kt0 = c0 + kw;
+            const rsrc_t wr = make_rsrc(rb_tiles, rb_ok ? (unsigned)cend * kTileBytes : 0u);
+#pragma unroll
+            for (int t = 0; t < PF; ++t) wq[t] = buf_load16_stream(wr, (unsigned)(kt0 + t * p.KW) * kTileBytes + l * 16);
+            __syncthreads();                         // the previous stretch has been consumed
+        }
+        {   // stage x_q[:, c0*256 .. cend*256) into LDS, 16 bytes per thread and step
+            const int pieces_per_row = (cend - c0) * 16;
+            const int total = mcount * pieces_per_row;
+            int first = 0;
+            if (c0 == 0) {
+#pragma unroll
+                for (int u = 0; u < XPRE; ++u) {
+                    const int pc = tid + u * 256;
+                    const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
+                    if (pc < total) *reinterpret_cast<v4u *>(lds + row * p.xstride + col * 16) = xpre[u];
+                }
+                first = XPRE * 256;
+            }
+            for (int pc = first + tid; pc < total; pc += 256) {
+                const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
+                const v4u v = buf_load16(xr, (unsigned)row * p.Kp + (unsigned)c0 * kTileCols + col * 16);
+                *reinterpret_cast<v4u *>(lds + row * p.xstride + col * 16) = v;
+            }
+        }
+        __syncthreads();
+        while (true) {
+#pragma unroll
+            for (int t = 0; t < PF; ++t) {
+                const int kt = kt0 + t * p.KW;
+                if (kt < cend) {
+                    const unsigned char *xrow = lds + (kt - c0) * kTileCols + kb * 16;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4i a = widen_codes(wq[t][q]);
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) {
+                            v4i b = (v4i){0, 0, 0, 0};
+                            if (tt * 16 + ml < mcount)
+                                b = *reinterpret_cast<const v4i *>(xrow + (tt * 16 + ml) * p.xstride + q * 64);
+                            acc[tt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[tt], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+            kt0 += p.KW * PF;
+            if (kt0 >= cend) break;
+            const rsrc_t wr = make_rsrc(rb_tiles, rb_ok ? (unsigned)cend * kTileBytes : 0u);
+#pragma unroll
+            for (int t = 0; t < PF; ++t) wq[t] = buf_load16_stream(wr, (unsigned)(kt0 + t * p.KW) * kTileBytes + l * 16);
+        }
+    }
+
+    // ---- add the KW partial tiles of a row-block: its first wavefront ends up owning it
+    if (p.KW > 1) {
+        __syncthreads();                             // the activations in LDS are no longer needed
         v4i *red = reinterpret_cast<v4i *>(lds);
+        if (kw > 0) {
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) {
-            if (rt != w) {
-                const int slot = rt < w ? rt : rt - 1;
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) red[((w * 3 + slot) * TT + tt) * 64 + l] = acc[rt][tt];
-            }
+            for (int tt = 0; tt < TT; ++tt) red[((w * TT) + tt) * 64 + l] = acc[tt];
         }
         __syncthreads();
-    }
-    v4i mine[TT];
-    {
-        const v4i *red = reinterpret_cast<const v4i *>(lds);
+        if (kw > 0) return;
+        for (int o = 1; o < p.KW; ++o) {
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            v4i s = (v4i){0, 0, 0, 0};
-#pragma unroll
-            for (int rt = 0; rt < 4; ++rt)          // select acc[w][tt] without dynamic indexing
-                if (rt == w) s = acc[rt][tt];
-#pragma unroll
-            for (int ws = 0; ws < 4; ++ws) {
-                if (ws != w) {
-                    const int slot = w < ws ? w : w - 1;
-                    s += red[((ws * 3 + slot) * TT + tt) * 64 + l];
-                }
-            }
-            mine[tt] = s;
+            for (int tt = 0; tt < TT; ++tt) acc[tt] += red[(((w + o) * TT) + tt) * 64 + l];
         }
     }
-
-    const int n0 = rb * 64 + w * 16;                // this wavefront's 16 output rows
-    const int nl = n0 + 4 * (l >> 4);               // this lane's 4 consecutive rows
-    const int ml = l & 15;                          // this lane's token within a token tile
-
-    if (p.splits > 1) {
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            const int m = tt * 16 + ml;
-            if (m < mcount) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    __hip_atomic_fetch_add(&p.acc_ws[(size_t)m * p.Np + nl + v], mine[tt][v], __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const int old = __hip_atomic_fetch_add(&p.counters[rb], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            const int last = old == p.splits - 1;
-            if (last) __hip_atomic_exchange(&p.counters[rb], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            sh_last = last;
-        }
-        __syncthreads();
-        if (!sh_last) return;
-        __threadfence();
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            const int m = tt * 16 + ml;
-            if (m < mcount) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    mine[tt][v] = __hip_atomic_exchange(&p.acc_ws[(size_t)m * p.Np + nl + v], 0, __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    }
-
-    if (n0 >= p.N) return;                          // padding rows only
+    if (!rb_ok || n0 >= L.N) return;
 
     // ---- correction up-projection: corr[m,n] = sum_j B[n,j] h[m,j] on the f16 MFMA
     v4f corr[TT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) corr[tt] = (v4f){0.f, 0.f, 0.f, 0.f};
-    if (p.rank > 0) {
-        const int brow = n0 + (l & 15);
-        const bool brow_ok = brow < p.N;
-        const _Float16 *bptr = p.B + (size_t)(brow_ok ? brow : 0) * p.rank;
-        const bool bvec = (p.rank % 8) == 0;
-        for (int js = 0; js < p.hstride / 32; ++js) {
-            const int j0 = js * 32 + (l >> 4) * 8;
-            v8h a = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (brow_ok) {
-                if (bvec) {
-                    if (j0 < p.rank) a = *reinterpret_cast<const v8h *>(bptr + j0);
-                } else {
+    if (L.rank > 0) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (j0 + e < p.rank) a[e] = bptr[j0 + e];
+        for (int js = 0; js < JS; ++js) {
+            if (js * 32 < L.hstride) {
+                const int j0 = js * 32 + kb * 8;
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const int m = tt * 16 + ml;
+                    v8h b = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (m < mcount) b = *reinterpret_cast<const v8h *>(hs + m * L.hstride + j0);
+                    corr[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(breg[js], b, corr[tt], 0, 0, 0);
                 }
-            }
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                const int m = tt * 16 + ml;
-                v8h b = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (m < mcount) b = *reinterpret_cast<const v8h *>(p.h16 + (size_t)(m0 + m) * p.hstride + j0);
-                corr[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, corr[tt], 0, 0, 0);
             }
         }
     }
 
     // ---- dequantise, gate, store
-    const float s_w = *p.s_w;
-    float g[4] = {0.f, 0.f, 0.f, 0.f};
-    if (p.rank > 0) {
+    float gate[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            if (nl + v < p.N) g[v] = tanhf((float)p.alpha[nl + v]);
-    }
-    const bool nvec = (p.N % 4) == 0;
+    for (int v = 0; v < 4; ++v) gate[v] = L.rank > 0 ? tanhf(alpha_f[v]) : 0.f;
+    const bool nvec = (L.N % 4) == 0;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         const int m = tt * 16 + ml;
         if (m >= mcount) continue;
         const size_t mg = (size_t)(m0 + m);
-        const float scale = p.s_x[mg] * s_w;
-        const int rs = p.rowsum[mg];
+        const float scale = sx_pre[tt] * s_w;
+        const int rs = rs_pre[tt];
         int a[4];
         v4h o;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            a[v] = mine[tt][v] - rs;
-            o[v] = (_Float16)((float)a[v] * scale + g[v] * corr[tt][v]);
+            a[v] = acc[tt][v] - rs;
+            o[v] = (_Float16)((float)a[v] * scale + gate[v] * corr[tt][v]);
         }
-        if (nvec && nl + 3 < p.N) {
-            *reinterpret_cast<v4h *>(p.y + mg * p.N + nl) = o;
-            if (p.acc_debug) *reinterpret_cast<v4i *>(p.acc_debug + mg * p.N + nl) = (v4i){a[0], a[1], a[2], a[3]};
+        if (nvec && nl + 3 < L.N) {
+            *reinterpret_cast<v4h *>(L.y + mg * L.N + nl) = o;
+            if (L.acc_debug) *reinterpret_cast<v4i *>(L.acc_debug + mg * L.N + nl) = (v4i){a[0], a[1], a[2], a[3]};
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                if (nl + v < p.N) {
-                    p.y[mg * p.N + nl + v] = o[v];
-                    if (p.acc_debug) p.acc_debug[mg * p.N + nl + v] = a[v];
+                if (nl + v < L.N) {
+                    L.y[mg * L.N + nl + v] = o[v];
+                    if (L.acc_debug) L.acc_debug[mg * L.N + nl + v] = a[v];
                 }
             }
         }
@@ -263,64 +311,60 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p)
 }
 
 int g_target_wgs = 512;
+constexpr int kDecodeLdsBudget = 64 * 1024;
 
 }  // namespace
 
 void set_decode_target_wgs(int v) { g_target_wgs = v > 0 ? v : 512; }
 
-hipError_t launch_decode(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
-                         hipStream_t st)
+// Fills in the launch shape of a group whose layers, activations and outputs are set.
+hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
 {
-    DecodeParams p;
-    p.packed = reinterpret_cast<const v4u *>(L.W_packed);
-    p.xq = ws.xq;
-    p.s_x = ws.s_x;
-    p.rowsum = ws.rowsum;
-    p.s_w = L.s_w;
-    p.B = reinterpret_cast<const _Float16 *>(L.B_f16);
-    p.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-    p.h16 = ws.h16;
-    p.y = y;
-    p.acc_debug = acc_debug;
-    p.acc_ws = ws.acc;
-    p.counters = ws.counters;
-    p.M = M;
-    p.N = L.d_out;
-    p.Np = round_up(L.d_out, kTile);
-    p.Kp = round_up(L.d_in, kTile);
-    p.KS = p.Kp / kTile;
-    p.rank = L.rank;
-    p.hstride = h_stride(L.rank);
-
-    const int RB = p.Np / kTile;
-    const int cols = (M + kMaxDecodeM - 1) / kMaxDecodeM;
-    int splits = 1;
-    const bool can_split = cols == 1 && RB <= kNumCounters / 2 &&
-                           (size_t)round_up(M, 16) * p.Np * sizeof(int32_t) <= kAccZeroBytes;
-    if (can_split) {
-        splits = (g_target_wgs + RB - 1) / RB;
-        if (splits > p.KS / 4) splits = p.KS / 4;   // at least one tile per wavefront
-        if (splits < 1) splits = 1;
+    const int M = p.M;
+    p.Kp = round_up(d_in, kTileCols);
+    p.KT = p.Kp / kTileCols;
+    int rb_total = 0, hstride_max = 32;
+    for (int g = 0; g < p.G; ++g) {
+        rb_total += p.L[g].RBn;
+        if (p.L[g].hstride > hstride_max) hstride_max = p.L[g].hstride;
     }
-    p.ks_per_split = (p.KS + splits - 1) / splits;
-    p.splits = (p.KS + p.ks_per_split - 1) / p.ks_per_split;
+    // the widest row coverage per workgroup that still gives the chip enough workgroups
+    // and leaves each wavefront a short run of tiles
+    p.RW = 4;
+    while (p.RW > 1 && ((rb_total + p.RW - 1) / p.RW < g_target_wgs || p.KT > 16)) p.RW /= 2;
+    while (p.RW < 4 && p.KT < 4 / p.RW) p.RW *= 2;   // no more wavefronts per row-block than tiles
+    p.KW = 4 / p.RW;
+    int wgs = 0;
+    for (int g = 0; g < p.G; ++g) {
+        p.wg_start[g] = wgs;
+        wgs += (p.L[g].RBn + p.RW - 1) / p.RW;
+    }
+    p.wg_start[p.G] = wgs;
 
-    const dim3 grid(RB * p.splits, cols), block(256);
-    const int mt = cols > 1 ? 4 : (M + 15) / 16;
+    const int cols = (M + kMaxDecodeM - 1) / kMaxDecodeM;
+    const int mrows = cols > 1 ? kMaxDecodeM : M;
+    const int mt = (mrows + 15) / 16;
+    const size_t hbytes = (size_t)mrows * hstride_max * sizeof(_Float16);
+    // stretch of d_in staged in LDS: as long as fits the budget (whole rows for small M)
+    int ct = (int)(((kDecodeLdsBudget - hbytes) / mrows - 16) / kTileCols);
+    if (ct > p.KT) ct = p.KT;
+    if (ct < 1) ct = 1;
+    p.CT = ct;
+    p.xstride = ct * kTileCols + 16;
+    size_t stage = (size_t)mrows * p.xstride;
+    const size_t red = (size_t)4 * mt * 64 * 16;
+    if (stage < red) stage = red;
+    p.h_off = (int)stage;
+    const size_t lds = stage + hbytes;
+
+    const dim3 grid(wgs, cols), block(256);
     switch (mt) {
-        case 1: hipLaunchKernelGGL(decode_kernel<1>, grid, block, 0, st, p); break;
-        case 2: hipLaunchKernelGGL(decode_kernel<2>, grid, block, 0, st, p); break;
-        case 3: hipLaunchKernelGGL(decode_kernel<3>, grid, block, 0, st, p); break;
-        default: hipLaunchKernelGGL(decode_kernel<4>, grid, block, 0, st, p); break;
+        case 1: hipLaunchKernelGGL(decode_kernel<1>, grid, block, lds, st, p); break;
+        case 2: hipLaunchKernelGGL(decode_kernel<2>, grid, block, lds, st, p); break;
+        case 3: hipLaunchKernelGGL(decode_kernel<3>, grid, block, lds, st, p); break;
+        default: hipLaunchKernelGGL(decode_kernel<4>, grid, block, lds, st, p); break;
     }
     return hipGetLastError();
-}
-
-// Until the dedicated MFMA prefill kernel lands, large M runs as columns of 64 tokens.
-hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
-                          hipStream_t st)
-{
-    return launch_decode(ws, M, L, y, acc_debug, st);
 }
 
 }  // namespace hgf

@@ -10,9 +10,11 @@
 
 namespace hgf {
 
-constexpr int kTile = 64;            // packing granule in both dimensions
-constexpr int kTileBytes = 1024;     // one 64x64 tile of 2-bit codes
+constexpr int kTileRows = 16;        // a packed tile covers 16 rows ...
+constexpr int kTileCols = 256;       // ... by 256 columns of 2-bit codes
+constexpr int kTileBytes = 1024;
 constexpr int kMaxDecodeM = 64;      // decode kernel handles up to 4 token tiles of 16
+constexpr int kMaxGroup = 4;         // layers reading the same activations launched together
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
@@ -20,6 +22,47 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+
+// ---- branch-free guarded loads ---------------------------------------------------------
+// A load inside a conditional makes the compiler wait for every outstanding load at the
+// join, which serialises the memory pipeline.  These helpers go through a buffer
+// descriptor instead: an offset at or beyond the descriptor's size reads as zero, so a
+// guard becomes a select on the offset and the loads stay back to back.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOob = 0xFFFFFF00u;         // beyond any descriptor in this library
+__device__ inline rsrc_t make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ inline v4u buf_load16(rsrc_t r, unsigned off, bool ok = true)
+{
+    return __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(r, (int)(ok ? off : kOob), 0, 0));
+}
+__device__ inline v4u buf_load16_stream(rsrc_t r, unsigned off)   // read-once data: non-temporal
+{
+    return __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2));
+}
+__device__ inline unsigned buf_load4(rsrc_t r, unsigned off, bool ok = true)
+{
+    return (unsigned)__builtin_amdgcn_raw_buffer_load_b32(r, (int)(ok ? off : kOob), 0, 0);
+}
+__device__ inline unsigned short buf_load2(rsrc_t r, unsigned off, bool ok = true)
+{
+    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)(ok ? off : kOob), 0, 0);
+}
+__device__ inline _Float16 half_bits(unsigned short u) { return __builtin_bit_cast(_Float16, u); }
+// Eight consecutive fp16 of a row-major matrix behind `r`, starting at element `elem`;
+// elements at column >= cols_left read as zero.  VEC: the eight are 16-byte aligned and
+// all in range or all out.
+template <bool VEC>
+__device__ inline v8h buf_load8h(rsrc_t r, unsigned elem, int cols_left, bool ok)
+{
+    if (VEC) return __builtin_bit_cast(v8h, buf_load16(r, elem * 2u, ok && cols_left > 0));
+    v8h v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = half_bits(buf_load2(r, (elem + e) * 2u, ok && e < cols_left));
+    return v;
+}
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -39,8 +82,10 @@ struct Workspace {
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
-    _Float16 *h16;       // [M, h_stride] SiLU(A x), zero padded
-    float *hpart;        // [splits, M16, rp]
+    _Float16 *h16;       // large M: [M, h_stride] SiLU(A x), zero padded
+    float *hpart;        // large M: [splits, M16, rp] scratch of the split down-projection
+    float *hslices;      // decode: kMaxGroup x [S, M, h_stride] fp32 partial sums of A x
+    size_t hslices_each; // bytes per layer of a group
     double *wsum;        // [kWsumBlocks]
     size_t bytes;        // total bytes needed
 };
@@ -60,6 +105,48 @@ inline int h_stride(int rank)       // row stride of h16 in elements (multiple o
     return s < 32 ? 32 : s;
 }
 
+// ---- grouped launches: up to kMaxGroup layers that read the same activations ----------
+
+struct ProLayer {
+    const _Float16 *A;   // [rank, K]
+    float *hpart;        // [S, M, rp] fp32 partial sums of A x
+    int rank, rp;
+};
+struct ProParams {
+    const _Float16 *x;
+    int8_t *xq;
+    float *s_x;
+    int32_t *rowsum;
+    int M, K, Kp, G;
+    ProLayer L[kMaxGroup];
+    int job_start[kMaxGroup + 1];
+    int S, pairs, pairs_per_slice;   // slices of d_in; 64-column steps in all and per slice
+};
+
+struct DecLayer {
+    const v4u *packed;
+    const float *s_w;
+    const _Float16 *B;
+    const _Float16 *alpha;
+    const float *hpart;      // hmode 0: [S, M, hstride] partial sums of A x
+    const _Float16 *h16;     // hmode 1: [M, hstride] SiLU(A x)
+    _Float16 *y;
+    int32_t *acc_debug;
+    int N, RBn, rank, hstride;
+};
+struct DecodeParams {
+    const int8_t *xq;
+    const float *s_x;
+    const int32_t *rowsum;
+    int M, Kp, KT, G;
+    DecLayer L[kMaxGroup];
+    int wg_start[kMaxGroup + 1];
+    int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4)
+    int CT, xstride;         // tiles of d_in staged in LDS at a time; bytes per staged row
+    int S, hmode;            // slices of the correction partial sums; see DecLayer
+    int h_off;               // byte offset of the SiLU(A x) rows in LDS
+};
+
 // ---- kernel launchers (each validates nothing: the ABI layer has done it) -----------
 hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_out, hipStream_t st);
 hipError_t launch_pack(const float *W, int N, int K, const float *s_w, uint32_t *packed, hipStream_t st);
@@ -71,10 +158,9 @@ int corr_splits(int M, int K);
 size_t corr_scratch_bytes(int M, int K, int rank);
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, int rank,
                             const Workspace &ws, hipStream_t st);
-hipError_t launch_decode(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
-                         hipStream_t st);
+int prologue_slices(int M, int K);
+hipError_t launch_prologue(ProParams &p, hipStream_t st);
+hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
 void set_decode_target_wgs(int v);
-hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
-                          hipStream_t st);
 
 }  // namespace hgf

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const _Float16 *__restric
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st)
 {
-    const int Kp = round_up(K, kTile);
+    const int Kp = round_up(K, kTileCols);
     if (K % 8 == 0)
         hipLaunchKernelGGL(quantize_kernel<true>, dim3(M), dim3(256), 0, st, x, K, Kp, xq, s_x, rowsum);
     else

@@ -56,20 +56,28 @@ __device__ inline uint32_t ternary_code(float w, float inv)
     return (uint32_t)((int)q + 1);
 }
 
+// Position of packed word `idx`: tile = idx/256; within the tile lane l = (idx%256)/4 and
+// word t = idx%4 hold row 16*rb + (l%16), columns 256*kt + 64*t + 16*(l/16) + 0..15.
+__device__ inline void word_position(size_t idx, int KT, int &row, int &kbase)
+{
+    const size_t tile = idx >> 8;
+    const int within = (int)(idx & 255);
+    const int l = within >> 2, t = within & 3;
+    const int rb = (int)(tile / KT), kt = (int)(tile % KT);
+    row = rb * kTileRows + (l & 15);
+    kbase = kt * kTileCols + t * 64 + (l >> 4) * 16;
+}
+
 // One thread per packed 32-bit word: 16 codes of one row, 16 consecutive columns.
-__global__ __launch_bounds__(256) void pack_kernel(const float *__restrict__ W, int N, int K, int KS,
+__global__ __launch_bounds__(256) void pack_kernel(const float *__restrict__ W, int N, int K, int KT,
                                                    const float *__restrict__ s_w,
                                                    uint32_t *__restrict__ packed, size_t nwords)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nwords) return;
     const float inv = 1.0f / *s_w;
-    const size_t tile = idx >> 8;
-    const int within = (int)(idx & 255);
-    const int l = within >> 2, q = within & 3;
-    const int rb = (int)(tile / KS), ks = (int)(tile % KS);
-    const int row = rb * kTile + q * 16 + (l & 15);
-    const int kbase = ks * kTile + (l >> 4) * 16;
+    int row, kbase;
+    word_position(idx, KT, row, kbase);
     uint32_t word = 0;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -85,17 +93,13 @@ __global__ __launch_bounds__(256) void pack_kernel(const float *__restrict__ W, 
 }
 
 // One thread per packed word, writing its 16 values back as int8 -1/0/+1.
-__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *__restrict__ packed, int N, int K, int KS,
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *__restrict__ packed, int N, int K, int KT,
                                                      int8_t *__restrict__ T, size_t nwords)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nwords) return;
-    const size_t tile = idx >> 8;
-    const int within = (int)(idx & 255);
-    const int l = within >> 2, q = within & 3;
-    const int rb = (int)(tile / KS), ks = (int)(tile % KS);
-    const int row = rb * kTile + q * 16 + (l & 15);
-    const int kbase = ks * kTile + (l >> 4) * 16;
+    int row, kbase;
+    word_position(idx, KT, row, kbase);
     if (row >= N) return;
     const uint32_t word = packed[idx];
 #pragma unroll
@@ -126,18 +130,18 @@ hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_ou
 
 hipError_t launch_pack(const float *W, int N, int K, const float *s_w, uint32_t *packed, hipStream_t st)
 {
-    const int KS = round_up(K, kTile) / kTile;
-    const size_t nwords = (size_t)(round_up(N, kTile) / kTile) * KS * 256;
-    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st, W, N, K, KS, s_w,
+    const int KT = round_up(K, kTileCols) / kTileCols;
+    const size_t nwords = (size_t)(round_up(N, kTileRows) / kTileRows) * KT * 256;
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st, W, N, K, KT, s_w,
                        packed, nwords);
     return hipGetLastError();
 }
 
 hipError_t launch_unpack(const uint32_t *packed, int N, int K, int8_t *T, hipStream_t st)
 {
-    const int KS = round_up(K, kTile) / kTile;
-    const size_t nwords = (size_t)(round_up(N, kTile) / kTile) * KS * 256;
-    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st, packed, N, K, KS,
+    const int KT = round_up(K, kTileCols) / kTileCols;
+    const size_t nwords = (size_t)(round_up(N, kTileRows) / kTileRows) * KT * 256;
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st, packed, N, K, KT,
                        T, nwords);
     return hipGetLastError();
 }

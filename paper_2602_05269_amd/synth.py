@@ -122,21 +122,34 @@ def make_custom(seed: int, M: int, d_in: int, d_out: int, rank: int, act: str = 
             "rank": rank}
 
 
-def stack_wiring(cfg: int) -> List[Tuple[int, int, int, int]]:
-    """(layer, proj, src_slot, dst_slot) for a configuration run as a chain of linears.
+def stack_wiring(cfg: int, chained: bool = True, n_layers: int | None = None):
+    """(layer, proj, src_slot, dst_slot) for a configuration run as a list of linears, and
+    the dict {slot: layer} of the slots that hold fresh inputs.
 
-    Slot 0 holds the input.  Per block: q, k, v read the block input; o reads v's
-    output; up and gate read o's output; down reads up's output and its output is
-    the next block's input.  Every linear writes a slot of its own, so each
-    layer's input and output stay available for checking.  A configuration
-    without q/k/v/o (up, gate, down only) has up and gate read the block input.
+    Per block: q, k, v read the block input; o reads v's output; up and gate read o's
+    output; down reads up's output.  Every linear writes a slot of its own, so each
+    layer's input and output stay available for checking.  A configuration without
+    q/k/v/o (up, gate, down only) has up and gate read the block input.
+
+    chained=True : slot 0 holds the only input and each block reads the previous block's
+                   `down` output -- a pure chain of linears (no residuals or norms, which
+                   are outside the layer), whose values shrink block by block.
+    n_layers overrides the configuration's number of blocks (the benchmark repeats a
+    one-block configuration over many distinct weight instances).
+    chained=False: every block reads a fresh synthetic input slot of its own, so every
+                   linear sees activations of a healthy magnitude (used for parity).
     """
     c = CONFIGS[cfg]
     names = [p.name for p in c.projections]
     wiring = []
+    inputs = {0: 0}
     block_in = 0
     nxt = 1
-    for layer in range(c.n_layers):
+    for layer in range(n_layers if n_layers is not None else c.n_layers):
+        if layer > 0 and not chained:
+            block_in = nxt
+            inputs[block_in] = layer
+            nxt += 1
         out = {}
         for pi, n in enumerate(names):
             if n in ("q", "k", "v", "lin"):
@@ -152,5 +165,6 @@ def stack_wiring(cfg: int) -> List[Tuple[int, int, int, int]]:
             out[n] = nxt
             wiring.append((layer, pi, src, nxt))
             nxt += 1
-        block_in = out.get("down", out[names[-1]])
-    return wiring
+        if chained:
+            block_in = out.get("down", out[names[-1]])
+    return wiring, inputs

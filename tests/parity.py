@@ -56,11 +56,13 @@ class GpuLayer:
 
     def oracle(self, x: np.ndarray, rows=None):
         c = self.case
-        T, A, B, alpha = self.T_ref, c["A"], c["B"], c["alpha"]
-        if rows is not None:
-            T, B, alpha = T[rows], B[rows], alpha[rows]
+        T, A, B, alpha = self.T_ref, c.get("A"), c.get("B"), c.get("alpha")
         if self.rank == 0:
             A = B = alpha = None
+        if rows is not None:
+            T = T[rows]
+            if self.rank:
+                B, alpha = B[rows], alpha[rows]
         return orc.linear_forward(x, T, self.s_w_ref, A, B, alpha)
 
     def check_forward(self, x: np.ndarray, rows=None, tokens=None, ws=None):

@@ -294,6 +294,8 @@ def test_synth_configs_match_the_benchmark_shapes():
     c4 = synth.CONFIGS[4]
     assert [(p.name, p.d_in, p.d_out) for p in c4.projections] == [
         ("up", 4096, 11008), ("gate", 4096, 11008), ("down", 11008, 4096)]
-    assert len(synth.stack_wiring(1)) == 56
-    w = synth.stack_wiring(1)
+    w, inputs = synth.stack_wiring(1)
+    assert len(w) == 56 and inputs == {0: 0}
     assert w[0][2:] == (0, 1) and w[3][2] == w[2][3] and w[6][2] == w[4][3] and w[7][2] == w[6][3]
+    w2, inputs2 = synth.stack_wiring(1, chained=False)
+    assert len(w2) == 56 and len(inputs2) == 8 and w2[7][2] in inputs2 and w2[7][2] != w2[6][3]
