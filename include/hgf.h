@@ -52,11 +52,11 @@ int hgf_version(void);
 
 /* ---------------------------------------------------------------- sizes (host only) */
 
-/* d_in rounded up to the packing granule (256).  Rows of x_q have this many bytes;
+/* d_in rounded up to the packing granule (128).  Rows of x_q have this many bytes;
  * the padding bytes are written as 0 by hgf_quantize_activations. */
 int hgf_padded_k(int d_in);
 /* Bytes of the packed 2-bit weight buffer of a [d_out, d_in] matrix (d_out padded to
- * 16, d_in to 256; padding decodes to 0).  0 on invalid sizes. */
+ * 32, d_in to 128; padding decodes to 0).  0 on invalid sizes. */
 size_t hgf_packed_weight_bytes(int d_out, int d_in);
 /* Bytes of workspace that any call with M <= M_max, d_in <= d_in_max,
  * d_out <= d_out_max, rank <= rank_max needs.  0 on invalid sizes. */
@@ -80,13 +80,14 @@ hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *str
  *   packed_out hgf_packed_weight_bytes(d_out, d_in) bytes
  *   s_w_out    one fp32
  *
- * Packed layout: tiles of 16 rows x 256 columns, 1 KiB each, ordered row-block major
+ * Packed layout: tiles of 32 rows x 128 columns, 1 KiB each, ordered row-block major
  * then along d_in, so one row-block's tiles are contiguous and a wavefront reads a tile
  * with one 16-byte load per lane.  Within a tile, bytes 16*l + 4*t .. +3 (l = 0..63,
- * t = 0..3) are a little-endian 32-bit word holding the 16 codes of row (l mod 16),
- * columns 64*t + 16*(l div 16) + 0..15; column offset 4*s + b sits at bits
- * [8*b + 2*s, 8*b + 2*s + 1].  A code is T + 1 (0, 1 or 2; 3 never occurs); padding rows
- * and columns hold code 1.
+ * t = 0..3) are a little-endian 32-bit word holding the 16 codes of row (l mod 32),
+ * columns 32*t + 16*(l div 32) + 0..15; column offset 4*s + b sits at bits
+ * [8*b + 2*s, 8*b + 2*s + 1] (so a shift by 2*s and a mask give the four int8 of one
+ * register of a 32x32x32 int8 MFMA operand).  A code is T + 1 (0, 1 or 2; 3 never
+ * occurs); padding rows and columns hold code 1.
  */
 hgf_status hgf_quantize_pack_weights(const float *W, int d_out, int d_in, void *packed_out,
                                      float *s_w_out, void *workspace, size_t workspace_bytes,

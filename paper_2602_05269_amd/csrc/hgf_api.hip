@@ -149,7 +149,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
 }
 
 // Large M: per layer, quantiser (shared by the group), split down-projection with SiLU,
-// then the main kernel in columns of 64 tokens.
+// then the int8 MFMA prefill kernel.
 hgf_status run_large_layer(const void *x, int M, const hgf_layer &L, void *y, int32_t *acc_debug,
                            const Workspace &ws, bool quantise, hipStream_t st)
 {
@@ -159,29 +159,8 @@ hgf_status run_large_layer(const void *x, int M, const hgf_layer &L, void *y, in
     if (L.rank > 0 &&
         launch_corr_down(xh, M, L.d_in, reinterpret_cast<const _Float16 *>(L.A_f16), L.rank, ws, st) != hipSuccess)
         return HGF_ERR_DEVICE;
-    DecodeParams dp;
-    dp.xq = ws.xq;
-    dp.s_x = ws.s_x;
-    dp.rowsum = ws.rowsum;
-    dp.M = M;
-    dp.G = 1;
-    dp.hmode = 1;
-    dp.S = 1;
-    DecLayer &D = dp.L[0];
-    D.packed = reinterpret_cast<const v4u *>(L.W_packed);
-    D.s_w = L.s_w;
-    D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
-    D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-    D.hpart = nullptr;
-    D.h16 = ws.h16;
-    D.y = reinterpret_cast<_Float16 *>(y);
-    D.acc_debug = acc_debug;
-    D.N = L.d_out;
-    D.RBn = round_up(L.d_out, kTileRows) / kTileRows;
-    D.rank = L.rank;
-    D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
     ProfileScope prof(1, st);
-    return from_hip(launch_decode(dp, L.d_in, st));
+    return from_hip(launch_prefill(ws, M, L, reinterpret_cast<_Float16 *>(y), acc_debug, st));
 }
 
 }  // namespace

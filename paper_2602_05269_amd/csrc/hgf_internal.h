@@ -10,8 +10,8 @@
 
 namespace hgf {
 
-constexpr int kTileRows = 16;        // a packed tile covers 16 rows ...
-constexpr int kTileCols = 256;       // ... by 256 columns of 2-bit codes
+constexpr int kTileRows = 32;        // a packed tile covers 32 rows ...
+constexpr int kTileCols = 128;       // ... by 128 columns of 2-bit codes
 constexpr int kTileBytes = 1024;
 constexpr int kMaxDecodeM = 64;      // decode kernel handles up to 4 token tiles of 16
 constexpr int kMaxGroup = 4;         // layers reading the same activations launched together
@@ -20,6 +20,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
@@ -141,10 +142,10 @@ struct DecodeParams {
     int M, Kp, KT, G;
     DecLayer L[kMaxGroup];
     int wg_start[kMaxGroup + 1];
-    int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4)
+    int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4 or 8)
     int CT, xstride;         // tiles of d_in staged in LDS at a time; bytes per staged row
     int S, hmode;            // slices of the correction partial sums; see DecLayer
-    int h_off;               // byte offset of the SiLU(A x) rows in LDS
+    int h_off, g_off;        // byte offsets in LDS of the SiLU(A x) rows and of the tanh(alpha) table
 };
 
 // ---- kernel launchers (each validates nothing: the ABI layer has done it) -----------
@@ -162,5 +163,7 @@ int prologue_slices(int M, int K);
 hipError_t launch_prologue(ProParams &p, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
 void set_decode_target_wgs(int v);
+hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
+                          hipStream_t st);
 
 }  // namespace hgf

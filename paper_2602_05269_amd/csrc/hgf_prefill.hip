@@ -1,0 +1,275 @@
+// Prefill kernel (M > 64): the ternary x int8 contraction as a dense int8 MFMA GEMM,
+// fused with dequantisation, the rank-r up-projection and the gate.
+//
+// Algorithm 1 of the HGF paper, steps 3, 4, 7 and 8 (see hgf_decode.hip for the formulas).
+// At hundreds of tokens the layer is a dense contraction (4*M int8 ops per weight byte), so
+// it is tiled for the matrix cores: a workgroup of four wavefronts owns 256 output rows x
+// 128 tokens; each wavefront owns 64 rows (two packed row-blocks) x 128 tokens = 8
+// accumulator tiles of the 32x32x32 int8 MFMA (the full-rate int8 shape on gfx950: the
+// 16x16x64 shape issues at half the rate), so each widened weight operand (7 VALU ops)
+// feeds four MFMAs and each activation operand read from LDS feeds two.
+// Weights never touch LDS: a wavefront loads its own packed tiles (16 bytes per lane per
+// row-block per 128 columns), widens the 2-bit codes in registers and uses them as the
+// MFMA's row operand.  The quantised activations of the 128 tokens are loaded straight
+// into LDS (three buffers, requested two steps ahead, one barrier per 128 columns) and are
+// shared by the four wavefronts.  Codes are T+1; the per-token sum of x_q is subtracted in
+// the epilogue (integer-exact).
+#include "hgf_internal.h"
+
+namespace hgf {
+
+namespace {
+
+constexpr int kPN = 256;            // output rows per workgroup: four wavefronts x two row-blocks
+constexpr int kPM = 128;            // tokens per workgroup
+constexpr int kPG = kPM / 32;       // token groups of 32 per wavefront
+constexpr int kXP = kPM * kTileCols / (256 * 16);   // 16-byte activation pieces per thread and step
+
+struct PrefillParams {
+    const v4u *packed;
+    const int8_t *xq;
+    const float *s_x;
+    const int32_t *rowsum;
+    const float *s_w;
+    const _Float16 *B;
+    const _Float16 *alpha;
+    const _Float16 *h16;
+    _Float16 *y;
+    int32_t *acc_debug;
+    int M, N, Kp, KT, RBn, rank, hstride;
+    int NB;                        // workgroups along the output rows
+};
+
+__device__ inline v4i widen_codes(uint32_t w)
+{
+    v4i a;
+    a[0] = (int)(w & 0x03030303u);
+    a[1] = (int)((w >> 2) & 0x03030303u);
+    a[2] = (int)((w >> 4) & 0x03030303u);
+    a[3] = (int)((w >> 6) & 0x03030303u);
+    return a;
+}
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+// LDS image of a kPM x 128 activation tile: row r at byte 128*r, its eight 16-byte pieces
+// permuted by XOR with (r mod 8), so that lanes reading the same piece of consecutive rows
+// spread over the bank groups without padding (padding is impossible: an LDS-direct load
+// writes 64 lanes x 16 bytes contiguously).
+__device__ inline unsigned piece_slot(unsigned piece, unsigned row) { return piece ^ (row & 7u); }
+
+__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
+{
+    // three separately declared activation buffers: the compiler can then prove that an
+    // LDS-direct load into one does not alias the reads of another and leaves it in flight
+    __shared__ __attribute__((aligned(1024))) unsigned char xs0[kPM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs1[kPM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs2[kPM * kTileCols];
+    __shared__ float gs[kPN];                            // tanh(alpha) of the workgroup's rows
+
+    const int tid = threadIdx.x, l = tid & 63, jl = l & 31, hf = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nb = blockIdx.x % p.NB, mb = blockIdx.x / p.NB;
+    const int rb0 = nb * (kPN / kTileRows) + w * 2;      // this wavefront's first row-block
+    const int m0 = mb * kPM;
+    const int mrows = min(kPM, p.M - m0);
+
+    rsrc_t wr[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const bool ok = rb0 + rb < p.RBn;
+        wr[rb] = make_rsrc(p.packed + (size_t)(ok ? rb0 + rb : 0) * p.KT * 64, ok ? (unsigned)p.KT * kTileBytes : 0u);
+    }
+    const rsrc_t xr = make_rsrc(p.xq + (size_t)m0 * p.Kp, (unsigned)mrows * p.Kp);
+
+    {   // gate table
+        const rsrc_t ar = make_rsrc(p.alpha, p.rank > 0 ? (unsigned)p.N * 2u : 0u);
+        const int n = nb * kPN + tid;
+        const float a = (float)half_bits(buf_load2(ar, (unsigned)n * 2u, n < p.N));
+        gs[tid] = p.rank > 0 ? tanhf(a) : 0.f;
+    }
+
+    // Activation staging: instruction i of wavefront w fills LDS bytes [(4i+w) KiB, +1 KiB):
+    // lane L writes row 8(4i+w) + L/8, slot L%8, which holds piece slot ^ (row%8).  Rows
+    // beyond the last token lie outside the descriptor and arrive as zeros.
+    unsigned xsrc[kXP];
+#pragma unroll
+    for (int i = 0; i < kXP; ++i) {
+        const unsigned row = (unsigned)(4 * i + w) * 8 + (l >> 3);
+        xsrc[i] = row * p.Kp + piece_slot(l & 7, row) * 16;
+    }
+    auto stage = [&](unsigned char *buf, v4u (&wfill)[2], int kt) {   // request step kt
+        const bool ok = kt < p.KT;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) wfill[rb] = buf_load16(wr[rb], (unsigned)kt * kTileBytes + l * 16);
+#pragma unroll
+        for (int i = 0; i < kXP; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)(buf + (4 * i + w) * 1024), 16,
+                                                     (int)(ok ? xsrc[i] + (unsigned)kt * kTileCols : kOob), 0, 0, 0);
+    };
+    // Activation reads: lane (jl, hf) reads piece 2*t + hf of rows 32*tg + jl
+    unsigned xoff[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) xoff[t] = (unsigned)jl * kTileCols + piece_slot(2 * t + hf, jl) * 16;
+
+    v16i acc[2][kPG];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int tg = 0; tg < kPG; ++tg) acc[rb][tg] = (v16i){};
+
+    auto compute = [&](const unsigned char *xbase, const v4u (&wuse)[2]) {   // the 32 MFMAs of one step
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            v4i b[kPG];
+#pragma unroll
+            for (int tg = 0; tg < kPG; ++tg)
+                b[tg] = *reinterpret_cast<const v4i *>(xbase + xoff[t] + tg * 32 * kTileCols);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const v4i a = widen_codes(wuse[rb][t]);
+#pragma unroll
+                for (int tg = 0; tg < kPG; ++tg)
+                    acc[rb][tg] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[tg], acc[rb][tg], 0, 0, 0);
+            }
+        }
+    };
+
+    // Software pipeline, two steps (2 x 128 columns) ahead.  Every step issues kLoads vector
+    // memory operations per wavefront (2 weight loads + kXP LDS-direct loads).  A step:
+    //   wait until this wavefront's loads of step kt have landed (the kLoads of step kt+1 may
+    //   stay in flight); barrier: everyone's have, and everyone is done computing step kt-1;
+    //   request step kt+2 into the buffer step kt-1 used; compute step kt.
+    // The barrier is the bare instruction (the fence of __syncthreads would wait for all
+    // loads in flight); the empty asm statements keep the compiler from moving memory
+    // operations across it.  Beyond the last step the descriptors return zeros, never used.
+    constexpr int kLoads = 2 + kXP;
+    constexpr int kWaitOneStepInFlight = (kLoads & 0xF) | (7 << 4) | (15 << 8) | ((kLoads >> 4) << 14);
+#define HGF_STEP(XCUR, WCUR, XFILL, WFILL, KT)                    \
+    do {                                                          \
+        __builtin_amdgcn_s_waitcnt(kWaitOneStepInFlight);         \
+        asm volatile("" ::: "memory");                            \
+        __builtin_amdgcn_s_barrier();                             \
+        asm volatile("" ::: "memory");                            \
+        stage(XFILL, WFILL, (KT) + 2);                            \
+        __builtin_amdgcn_sched_barrier(0);                        \
+        compute(XCUR, WCUR);                                      \
+        __builtin_amdgcn_sched_barrier(0);                        \
+    } while (0)
+
+    v4u w0[2], w1[2], w2[2];
+    stage(xs0, w0, 0);
+    stage(xs1, w1, 1);
+    int kt = 0;
+    for (; kt + 2 < p.KT; kt += 3) {
+        HGF_STEP(xs0, w0, xs2, w2, kt);
+        HGF_STEP(xs1, w1, xs0, w0, kt + 1);
+        HGF_STEP(xs2, w2, xs1, w1, kt + 2);
+    }
+    if (kt < p.KT) HGF_STEP(xs0, w0, xs2, w2, kt);
+    if (kt + 1 < p.KT) HGF_STEP(xs1, w1, xs0, w0, kt + 1);
+#undef HGF_STEP
+    __syncthreads();                                 // gs is complete; drains the unused tail loads
+
+    // ---- epilogue: correction up-projection on the f16 MFMA, gate, dequantise, store.
+    //      Element 4*q + v of an accumulator is row 8*q + 4*hf + v of the row-block, for the
+    //      token of the lane.
+    const float s_w = *p.s_w;
+    float sx[kPG];
+    int rs[kPG];
+#pragma unroll
+    for (int tg = 0; tg < kPG; ++tg) {
+        const int m = m0 + tg * 32 + jl;
+        const bool ok = m < p.M;
+        sx[tg] = ok ? p.s_x[m] : 0.f;
+        rs[tg] = ok ? p.rowsum[m] : 0;
+    }
+    const rsrc_t br = make_rsrc(p.B, p.rank > 0 ? (unsigned)p.N * p.rank * 2u : 0u);
+    const rsrc_t hr = make_rsrc(p.h16, p.rank > 0 ? (unsigned)p.M * p.hstride * 2u : 0u);
+    const bool bvec = (p.rank % 8) == 0;
+    const bool nvec = (p.N % 4) == 0;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int n0 = (rb0 + rb) * kTileRows;
+        if (n0 >= p.N) break;                        // wavefront-uniform
+        v16f corr[kPG];
+#pragma unroll
+        for (int tg = 0; tg < kPG; ++tg) corr[tg] = (v16f){};
+        if (p.rank > 0) {
+            const int brow = n0 + jl;
+            for (int js = 0; js < p.hstride / 16; ++js) {
+                const int j0 = js * 16 + hf * 8;
+                const v8h a = bvec ? buf_load8h<true>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N)
+                                   : buf_load8h<false>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N);
+#pragma unroll
+                for (int tg = 0; tg < kPG; ++tg) {
+                    const int m = m0 + tg * 32 + jl;
+                    const v8h b = __builtin_bit_cast(v8h, buf_load16(hr, ((unsigned)m * p.hstride + j0) * 2u, m < p.M));
+                    corr[tg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, corr[tg], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int tg = 0; tg < kPG; ++tg) {
+            const int m = m0 + tg * 32 + jl;
+            if (m >= p.M) continue;
+            const float scale = sx[tg] * s_w;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r0 = 8 * q + 4 * hf;
+                const int nl = n0 + r0;
+                int a[4];
+                v4h o;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    a[v] = acc[rb][tg][4 * q + v] - rs[tg];
+                    o[v] = (_Float16)((float)a[v] * scale + gs[(w * 2 + rb) * kTileRows + r0 + v] * corr[tg][4 * q + v]);
+                }
+                const size_t at = (size_t)m * p.N + nl;
+                if (nvec && nl + 3 < p.N) {
+                    *reinterpret_cast<v4h *>(p.y + at) = o;
+                    if (p.acc_debug) *reinterpret_cast<v4i *>(p.acc_debug + at) = (v4i){a[0], a[1], a[2], a[3]};
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if (nl + v < p.N) {
+                            p.y[at + v] = o[v];
+                            if (p.acc_debug) p.acc_debug[at + v] = a[v];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
+                          hipStream_t st)
+{
+    PrefillParams p;
+    p.packed = reinterpret_cast<const v4u *>(L.W_packed);
+    p.xq = ws.xq;
+    p.s_x = ws.s_x;
+    p.rowsum = ws.rowsum;
+    p.s_w = L.s_w;
+    p.B = reinterpret_cast<const _Float16 *>(L.B_f16);
+    p.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
+    p.h16 = ws.h16;
+    p.y = y;
+    p.acc_debug = acc_debug;
+    p.M = M;
+    p.N = L.d_out;
+    p.Kp = round_up(L.d_in, kTileCols);
+    p.KT = p.Kp / kTileCols;
+    p.RBn = round_up(L.d_out, kTileRows) / kTileRows;
+    p.rank = L.rank;
+    p.hstride = h_stride(L.rank > 0 ? L.rank : 1);
+    p.NB = (L.d_out + kPN - 1) / kPN;
+    const int MB = (M + kPM - 1) / kPM;
+    hipLaunchKernelGGL(prefill_kernel, dim3(p.NB * MB), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace hgf

@@ -56,16 +56,16 @@ __device__ inline uint32_t ternary_code(float w, float inv)
     return (uint32_t)((int)q + 1);
 }
 
-// Position of packed word `idx`: tile = idx/256; within the tile lane l = (idx%256)/4 and
-// word t = idx%4 hold row 16*rb + (l%16), columns 256*kt + 64*t + 16*(l/16) + 0..15.
+// Position of packed word `idx`: tile = idx/256; within the tile, lane l = (idx%256)/4 and
+// word t = idx%4 hold row 32*rb + (l%32), columns 128*kt + 32*t + 16*(l/32) + 0..15.
 __device__ inline void word_position(size_t idx, int KT, int &row, int &kbase)
 {
     const size_t tile = idx >> 8;
     const int within = (int)(idx & 255);
     const int l = within >> 2, t = within & 3;
     const int rb = (int)(tile / KT), kt = (int)(tile % KT);
-    row = rb * kTileRows + (l & 15);
-    kbase = kt * kTileCols + t * 64 + (l >> 4) * 16;
+    row = rb * kTileRows + (l & 31);
+    kbase = kt * kTileCols + t * 32 + (l >> 5) * 16;
 }
 
 // One thread per packed 32-bit word: 16 codes of one row, 16 consecutive columns.

@@ -28,10 +28,10 @@ def test_library_exports_every_declared_symbol():
 
 def test_sizes():
     assert hb.hgf_version() >= 100
-    assert hb.hgf_padded_k(1) == 256 and hb.hgf_padded_k(256) == 256 and hb.hgf_padded_k(1365) == 1536
+    assert hb.hgf_padded_k(1) == 128 and hb.hgf_padded_k(256) == 256 and hb.hgf_padded_k(1365) == 1408
     assert hb.hgf_padded_k(0) == 0 and hb.hgf_padded_k(1 << 20) == 0
-    assert hb.hgf_packed_weight_bytes(16, 256) == 1024
-    assert hb.hgf_packed_weight_bytes(17, 257) == 4096
+    assert hb.hgf_packed_weight_bytes(32, 128) == 1024
+    assert hb.hgf_packed_weight_bytes(33, 129) == 4096
     assert hb.hgf_packed_weight_bytes(11008, 4096) == 11008 * 4096 // 4      # 2 bits per weight
     assert hb.hgf_packed_weight_bytes(0, 5) == 0
     a = hb.hgf_workspace_bytes(1, 512, 512, 32)
