@@ -24,10 +24,6 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
     ws.rowsum = reinterpret_cast<int32_t *>(take((size_t)M * 4));
     ws.h16 = reinterpret_cast<_Float16 *>(take((size_t)M * h_stride(rank > 0 ? rank : 1) * 2));
-    // scratch for the partial sums of the down-projection: a bound that is monotone in M and
-    // rank (the launcher uses at most min(32, ceil(768/tiles)) slices over `tiles` token tiles)
-    const size_t hpart = rank > 0 ? (size_t)(768 + (M + 15) / 16) * h_rank_tiles(rank) * 64 * 16 : 0;
-    ws.hpart = reinterpret_cast<float *>(take(hpart));
     // decode: per layer of a group at most 64 (slice, token) rows of h_stride partial sums
     ws.hslices_each = rank > 0 ? align256((size_t)64 * h_stride(rank) * sizeof(float)) : 0;
     ws.hslices = reinterpret_cast<float *>(take(ws.hslices_each * kMaxGroup));

@@ -1,12 +1,15 @@
-// Down-projection of the correction path: h16[m, j] = fp16( SiLU( sum_k A[j,k] x[m,k] ) ).
+// Down-projection of the correction path for many tokens (the prefill path):
+//   h16[m, j] = fp16( SiLU( sum_k A[j,k] x[m,k] ) ).
 //
 // Algorithm 1, steps 5-6 of the HGF paper (H <- X A; H <- SiLU(H)) on the UN-quantised
 // fp16 activations, with SiLU(h) = h * sigmoid(h) (Sec. 2.3, low-rank correction).
-// fp16 operands, fp32 accumulation on the 16x16x32 f16 MFMA: matrix rows are rank
-// indices, matrix columns are tokens.  One wavefront owns one tile of 16 tokens and one
-// slice of d_in and computes every rank tile for it, so x is read once.  With more than
-// one slice the partial sums go to scratch and the last wavefront to arrive for a token
-// tile adds them in slice order (deterministic), applies SiLU and writes fp16.
+// A skinny GEMM on the 32x32x16 f16 MFMA: matrix rows are rank indices (so a lane ends up
+// with four consecutive ranks of one token: 8-byte stores), matrix columns are tokens.
+// One workgroup of four wavefronts owns 32 tokens.  x and A are streamed through LDS in
+// stretches of KC columns with LDS-direct loads (whole row pieces, coalesced; double
+// buffered, requested one stretch ahead); each wavefront multiplies a quarter of the stretch
+// for every rank tile; the four partial tiles meet in LDS at the end and the first
+// wavefront adds them in order (deterministic), applies SiLU and writes fp16.
 #include "hgf_internal.h"
 
 namespace hgf {
@@ -17,136 +20,163 @@ struct CorrParams {
     const _Float16 *x;
     const _Float16 *A;
     _Float16 *h16;
-    float *hpart;
-    int32_t *counters;
     int M, K, rank, hstride;
-    int splits, ksteps, ksteps_per_split;   // k-steps of 32 columns
+    int steps;                                  // stretches of KC columns
 };
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 __device__ inline float silu(float h) { return h / (1.0f + expf(-h)); }
 
-template <bool VEC>
-__device__ inline v8h load8(const _Float16 *row, int k0, int K, bool row_ok)
+// Staged rows are permuted in units of 16 bytes by XOR with (row mod 8), so that the lanes
+// reading the same piece of consecutive rows spread over the banks.
+__device__ inline unsigned slot_of(unsigned piece, unsigned row) { return piece ^ (row & 7u); }
+
+// RT: rank tiles of 32 covering the padded row of h16 (1, 2 or 4).  KC: columns per stretch.
+template <int RT, int KC>
+__global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
 {
-    v8h v = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (!row_ok) return v;
-    if (VEC) {
-        if (k0 < K) v = *reinterpret_cast<const v8h *>(row + k0);   // K % 8 == 0: whole vector in range
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (k0 + e < K) v[e] = row[k0 + e];
-    }
-    return v;
-}
+    constexpr int kRowB = KC * 2;               // bytes per staged row
+    constexpr int kPieces = kRowB / 16;         // 16-byte pieces per row = lanes per row of an LDS-direct load
+    constexpr int kRowsPerInst = 64 / kPieces;
+    constexpr int kXInst = 32 / kRowsPerInst / 4;        // LDS-direct loads per wavefront for x ...
+    constexpr int kAInst = RT * 32 / kRowsPerInst / 4;   // ... and for A, per stretch
+    // separately declared buffers: the compiler can prove an LDS-direct load into one stage
+    // does not alias the reads of the other and leaves it in flight
+    __shared__ __attribute__((aligned(1024))) unsigned char xs0[32 * kRowB], xs1[32 * kRowB];
+    __shared__ __attribute__((aligned(1024))) unsigned char as0[RT * 32 * kRowB], as1[RT * 32 * kRowB];
 
-template <int RTN, bool VEC>
-__global__ __launch_bounds__(64) void corr_down_kernel(CorrParams p)
-{
-    const int tt = blockIdx.x / p.splits, sp = blockIdx.x % p.splits;
-    const int l = threadIdx.x, i = l & 15, kb = l >> 4;
-    const int m = tt * 16 + i;
-    const bool m_ok = m < p.M;
-    const _Float16 *xrow = p.x + (size_t)(m_ok ? m : 0) * p.K;
+    const int tid = threadIdx.x, l = tid & 63, jl = l & 31, hf = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m0 = blockIdx.x * 32;
+    const int mrows = min(32, p.M - m0);
+    const rsrc_t xr = make_rsrc(p.x + (size_t)m0 * p.K, (unsigned)mrows * p.K * 2u);
+    const rsrc_t ar = make_rsrc(p.A, (unsigned)p.rank * p.K * 2u);
 
-    v4f acc[RTN];
+    // Staging: one instruction moves 1 KiB = kRowsPerInst rows; lane L writes row
+    // kRowsPerInst*ii + L/kPieces, slot L%kPieces.  Rows beyond the last token / rank lie
+    // outside the descriptors and arrive as zeros; columns beyond d_in are guarded (they
+    // would otherwise read the next row).
+    auto stage = [&](unsigned char *xb, unsigned char *ab, int st) {
+        const int k0 = st * KC;
 #pragma unroll
-    for (int rt = 0; rt < RTN; ++rt) acc[rt] = (v4f){0.f, 0.f, 0.f, 0.f};
-
-    const int ks0 = sp * p.ksteps_per_split;
-    const int ks1 = min(ks0 + p.ksteps_per_split, p.ksteps);
-    for (int ks = ks0; ks < ks1; ++ks) {
-        const int k0 = ks * 32 + kb * 8;
-        const v8h b = load8<VEC>(xrow, k0, p.K, m_ok);
-#pragma unroll
-        for (int rt = 0; rt < RTN; ++rt) {
-            const int j = rt * 16 + i;
-            const bool j_ok = j < p.rank;
-            const v8h a = load8<VEC>(p.A + (size_t)(j_ok ? j : 0) * p.K, k0, p.K, j_ok);
-            acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[rt], 0, 0, 0);
+        for (int i = 0; i < kXInst; ++i) {
+            const unsigned ii = 4 * i + w, row = kRowsPerInst * ii + l / kPieces;
+            const int col = k0 + (int)slot_of(l % kPieces, row) * 8;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)(xb + ii * 1024), 16,
+                                                     (int)(col < p.K ? (row * p.K + col) * 2u : kOob), 0, 0, 0);
         }
-    }
-
-    // acc[rt][v] holds rank index rt*16 + 4*(l/16) + v for token tt*16 + (l%16)
-    if (p.splits > 1) {
-        // Partial sums cross workgroups (and XCDs, whose L2 caches are not coherent with each
-        // other) as device-scope atomic stores and loads, which go to the point of coherence:
-        // no cache write-back or invalidate.  The arrival counter moves once they are acknowledged.
-        const int ntt = gridDim.x / p.splits;
-        float *mine = p.hpart + ((size_t)(sp * ntt + tt) * RTN) * 256;
 #pragma unroll
-        for (int rt = 0; rt < RTN; ++rt)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                __hip_atomic_store(&mine[(rt * 4 + v) * 64 + l], acc[rt][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_s_waitcnt(0);
-        int old = 0;
-        if (l == 0) old = __hip_atomic_fetch_add(&p.counters[tt], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        old = __shfl(old, 0, 64);
-        if (old != p.splits - 1) return;
-        if (l == 0) __hip_atomic_exchange(&p.counters[tt], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int rt = 0; rt < RTN; ++rt) acc[rt] = (v4f){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < p.splits; ++s) {
-            const float *part = p.hpart + ((size_t)(s * ntt + tt) * RTN) * 256;
-#pragma unroll
-            for (int rt = 0; rt < RTN; ++rt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    acc[rt][v] += __hip_atomic_load(&part[(rt * 4 + v) * 64 + l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = 0; i < kAInst; ++i) {
+            const unsigned ii = 4 * i + w, row = kRowsPerInst * ii + l / kPieces;
+            const int col = k0 + (int)slot_of(l % kPieces, row) * 8;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ar, (lds_ptr_t)(ab + ii * 1024), 16,
+                                                     (int)(col < p.K ? (row * p.K + col) * 2u : kOob), 0, 0, 0);
         }
+    };
+
+    v16f acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[rt] = (v16f){};
+
+    // Wavefront w multiplies columns (KC/4)*w .. of the stretch: KC/64 MFMA k-steps of 16;
+    // lane (jl, hf) reads piece (KC/32)*w + 2*u + hf of row jl (tokens) / 32*rt + jl (ranks).
+    auto compute = [&](const unsigned char *xb, const unsigned char *ab) {
+#pragma unroll
+        for (int u = 0; u < KC / 64; ++u) {
+            const unsigned piece = (KC / 32) * w + 2 * u + hf;
+            const v8h b = *reinterpret_cast<const v8h *>(xb + jl * kRowB + slot_of(piece, jl) * 16);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const unsigned row = rt * 32 + jl;
+                const v8h a = *reinterpret_cast<const v8h *>(ab + row * kRowB + slot_of(piece, row) * 16);
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[rt], 0, 0, 0);
+            }
+        }
+    };
+
+    // A step waits for its own stage only (the next one stays in flight), meets the others at
+    // a bare barrier, computes, meets them again (everyone is done reading) and requests the
+    // stage after next into the same buffers.
+    constexpr int kLoads = kXInst + kAInst;     // vector memory operations per wavefront and stage
+    constexpr int kWaitNextInFlight = (kLoads & 0xF) | (7 << 4) | (15 << 8) | ((kLoads >> 4) << 14);
+#define HGF_CSTEP(XC, AC, ST)                                  \
+    do {                                                       \
+        __builtin_amdgcn_s_waitcnt(kWaitNextInFlight);         \
+        asm volatile("" ::: "memory");                         \
+        __builtin_amdgcn_s_barrier();                          \
+        asm volatile("" ::: "memory");                         \
+        compute(XC, AC);                                       \
+        asm volatile("" ::: "memory");                         \
+        __builtin_amdgcn_s_barrier();                          \
+        asm volatile("" ::: "memory");                         \
+        stage(XC, AC, (ST) + 2);                               \
+    } while (0)
+    stage(xs0, as0, 0);
+    stage(xs1, as1, 1);
+    int st = 0;
+    for (; st + 1 < p.steps; st += 2) {
+        HGF_CSTEP(xs0, as0, st);
+        HGF_CSTEP(xs1, as1, st + 1);
+    }
+    if (st < p.steps) HGF_CSTEP(xs0, as0, st);
+#undef HGF_CSTEP
+    __syncthreads();                             // drains the unused tail loads; buffers are free
+
+    // ---- add the four partial tiles (through the A buffers), SiLU, store
+    // 4 KiB * RT each: wavefront 1 -> as0, 2 -> as1, 3 -> second part of as0
+    float *red = reinterpret_cast<float *>(w == 2 ? as1 : (w == 3 ? as0 + RT * 4096 : as0));
+    if (w > 0) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[(rt * 16 + e) * 64 + l] = acc[rt][e];
+    }
+    __syncthreads();
+    if (w > 0) return;
+#pragma unroll
+    for (int s = 1; s < 4; ++s) {
+        const float *part = reinterpret_cast<const float *>(s == 2 ? as1 : (s == 3 ? as0 + RT * 4096 : as0));
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[rt][e] += part[(rt * 16 + e) * 64 + l];
     }
 
-    if (!m_ok) return;
+    // acc[rt][4q+v]: rank rt*32 + 8q + 4hf + v of token m0 + jl
+    const int m = m0 + jl;
+    if (m >= p.M) return;
     _Float16 *hrow = p.h16 + (size_t)m * p.hstride;
 #pragma unroll
-    for (int rt = 0; rt < RTN; ++rt) {
-        const int j0 = rt * 16 + 4 * kb;
-        v4h o;
+    for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) o[v] = (j0 + v < p.rank) ? (_Float16)silu(acc[rt][v]) : (_Float16)0.0f;
-        *reinterpret_cast<v4h *>(hrow + j0) = o;
-    }
-    if (RTN * 16 < p.hstride) {   // rank <= 16: the upper half of the 32-wide row is padding
-        v4h z = {0, 0, 0, 0};
-        *reinterpret_cast<v4h *>(hrow + 16 + 4 * kb) = z;
+        for (int q = 0; q < 4; ++q) {
+            const int j0 = rt * 32 + 8 * q + 4 * hf;
+            v4h o;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] = (j0 + v < p.rank) ? (_Float16)silu(acc[rt][4 * q + v]) : (_Float16)0.0f;
+            *reinterpret_cast<v4h *>(hrow + j0) = o;
+        }
     }
 }
 
-template <int RTN>
-hipError_t launch_rtn(const CorrParams &p, int grid, bool vec, hipStream_t st)
+// d_in % 8 != 0 (rows not 16-byte aligned): one thread per (token, rank) pair with plain
+// loads.  Slow and simple, for odd shapes only.
+__global__ __launch_bounds__(256) void corr_down_ragged_kernel(CorrParams p)
 {
-    if (vec)
-        hipLaunchKernelGGL((corr_down_kernel<RTN, true>), dim3(grid), dim3(64), 0, st, p);
-    else
-        hipLaunchKernelGGL((corr_down_kernel<RTN, false>), dim3(grid), dim3(64), 0, st, p);
-    return hipGetLastError();
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)p.M * p.hstride) return;
+    const int m = (int)(idx / p.hstride), j = (int)(idx % p.hstride);
+    float h = 0.f;
+    if (j < p.rank) {
+        const _Float16 *xrow = p.x + (size_t)m * p.K, *arow = p.A + (size_t)j * p.K;
+        for (int k = 0; k < p.K; ++k) h += (float)arow[k] * (float)xrow[k];
+        h = silu(h);
+    }
+    p.h16[idx] = (_Float16)h;
 }
 
 }  // namespace
-
-// Number of d_in slices the launcher uses (also sizes the scratch for the partial sums).
-int corr_splits(int M, int K)
-{
-    const int ntt = (M + 15) / 16;
-    const int ksteps = (K + 31) / 32;
-    if (ntt > kNumCounters / 2) return 1;
-    int s = (768 + ntt - 1) / ntt;          // aim at ~768 wavefronts
-    if (s > kMaxHSplit) s = kMaxHSplit;
-    if (s > ksteps / 2) s = ksteps / 2;     // at least two k-steps per slice
-    if (s < 1) s = 1;
-    const int per = (ksteps + s - 1) / s;
-    return (ksteps + per - 1) / per;
-}
-
-size_t corr_scratch_bytes(int M, int K, int rank)
-{
-    if (rank <= 0) return 0;
-    const int s = corr_splits(M, K);
-    if (s == 1) return 0;
-    return (size_t)s * ((M + 15) / 16) * h_rank_tiles(rank) * 64 * sizeof(v4f);
-}
 
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, int rank, const Workspace &ws,
                             hipStream_t st)
@@ -155,24 +185,32 @@ hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, 
     p.x = x;
     p.A = A;
     p.h16 = ws.h16;
-    p.hpart = ws.hpart;
-    p.counters = ws.counters + kNumCounters / 2;
     p.M = M;
     p.K = K;
     p.rank = rank;
     p.hstride = h_stride(rank);
-    p.ksteps = (K + 31) / 32;
-    p.splits = corr_splits(M, K);
-    p.ksteps_per_split = (p.ksteps + p.splits - 1) / p.splits;
-    const int ntt = (M + 15) / 16;
-    const int grid = ntt * p.splits;
     const bool vec = (K % 8 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(A)) % 16 == 0);
-    switch (h_rank_tiles(rank)) {
-        case 1: return launch_rtn<1>(p, grid, vec, st);
-        case 2: return launch_rtn<2>(p, grid, vec, st);
-        case 4: return launch_rtn<4>(p, grid, vec, st);
-        default: return launch_rtn<8>(p, grid, vec, st);
+    if (!vec) {
+        const size_t n = (size_t)M * p.hstride;
+        hipLaunchKernelGGL(corr_down_ragged_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+        return hipGetLastError();
     }
+    const dim3 grid((M + 31) / 32), block(256);
+    switch (p.hstride / 32) {               // rank tiles cover the padded row: every column is written
+        case 1:
+            p.steps = (K + 255) / 256;
+            hipLaunchKernelGGL((corr_down_kernel<1, 256>), grid, block, 0, st, p);
+            break;
+        case 2:
+            p.steps = (K + 255) / 256;
+            hipLaunchKernelGGL((corr_down_kernel<2, 256>), grid, block, 0, st, p);
+            break;
+        default:
+            p.steps = (K + 127) / 128;
+            hipLaunchKernelGGL((corr_down_kernel<4, 128>), grid, block, 0, st, p);
+            break;
+    }
+    return hipGetLastError();
 }
 
 }  // namespace hgf

@@ -84,7 +84,6 @@ struct Workspace {
     float *s_x;
     int32_t *rowsum;
     _Float16 *h16;       // large M: [M, h_stride] SiLU(A x), zero padded
-    float *hpart;        // large M: [splits, M16, rp] scratch of the split down-projection
     float *hslices;      // decode: kMaxGroup x [S, M, h_stride] fp32 partial sums of A x
     size_t hslices_each; // bytes per layer of a group
     double *wsum;        // [kWsumBlocks]
@@ -155,8 +154,6 @@ hipError_t launch_unpack(const uint32_t *packed, int N, int K, int8_t *T, hipStr
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st);
-int corr_splits(int M, int K);
-size_t corr_scratch_bytes(int M, int K, int rank);
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, int rank,
                             const Workspace &ws, hipStream_t st);
 int prologue_slices(int M, int K);

@@ -11,7 +11,7 @@
 // Weights never touch LDS: a wavefront loads its own packed tiles (16 bytes per lane per
 // row-block per 128 columns), widens the 2-bit codes in registers and uses them as the
 // MFMA's row operand.  The quantised activations of the 128 tokens are loaded straight
-// into LDS (three buffers, requested two steps ahead, one barrier per 128 columns) and are
+// into LDS (four buffers, requested three steps ahead, one barrier per 128 columns) and are
 // shared by the four wavefronts.  Codes are T+1; the per-token sum of x_q is subtracted in
 // the epilogue (integer-exact).
 #include "hgf_internal.h"
@@ -58,13 +58,16 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 // writes 64 lanes x 16 bytes contiguously).
 __device__ inline unsigned piece_slot(unsigned piece, unsigned row) { return piece ^ (row & 7u); }
 
+// JS: steps of the 32x32x16 f16 MFMA over the (padded) rank = hstride / 16; 0 without correction.
+template <int JS>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 {
-    // three separately declared activation buffers: the compiler can then prove that an
+    // four separately declared activation buffers: the compiler can then prove that an
     // LDS-direct load into one does not alias the reads of another and leaves it in flight
     __shared__ __attribute__((aligned(1024))) unsigned char xs0[kPM * kTileCols];
     __shared__ __attribute__((aligned(1024))) unsigned char xs1[kPM * kTileCols];
     __shared__ __attribute__((aligned(1024))) unsigned char xs2[kPM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs3[kPM * kTileCols];
     __shared__ float gs[kPN];                            // tanh(alpha) of the workgroup's rows
 
     const int tid = threadIdx.x, l = tid & 63, jl = l & 31, hf = l >> 5;
@@ -87,6 +90,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
         const int n = nb * kPN + tid;
         const float a = (float)half_bits(buf_load2(ar, (unsigned)n * 2u, n < p.N));
         gs[tid] = p.rank > 0 ? tanhf(a) : 0.f;
+    }
+
+    // the weight scale and the per-token scales of this lane's tokens, requested now, used in the epilogue
+    const float s_w = *p.s_w;
+    float sx[kPG];
+    int rs[kPG];
+    {
+        const rsrc_t sr = make_rsrc(p.s_x, (unsigned)p.M * 4u);
+        const rsrc_t rr = make_rsrc(p.rowsum, (unsigned)p.M * 4u);
+#pragma unroll
+        for (int tg = 0; tg < kPG; ++tg) {
+            sx[tg] = __builtin_bit_cast(float, buf_load4(sr, (unsigned)(m0 + tg * 32 + jl) * 4u));
+            rs[tg] = (int)buf_load4(rr, (unsigned)(m0 + tg * 32 + jl) * 4u);
+        }
     }
 
     // Activation staging: instruction i of wavefront w fills LDS bytes [(4i+w) KiB, +1 KiB):
@@ -135,85 +152,112 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
         }
     };
 
-    // Software pipeline, two steps (2 x 128 columns) ahead.  Every step issues kLoads vector
+    // Software pipeline, three steps (3 x 128 columns) ahead.  Every step issues kLoads vector
     // memory operations per wavefront (2 weight loads + kXP LDS-direct loads).  A step:
-    //   wait until this wavefront's loads of step kt have landed (the kLoads of step kt+1 may
-    //   stay in flight); barrier: everyone's have, and everyone is done computing step kt-1;
-    //   request step kt+2 into the buffer step kt-1 used; compute step kt.
+    //   wait until this wavefront's loads of step kt have landed (the loads of steps kt+1 and
+    //   kt+2 may stay in flight); barrier: everyone's have, and everyone is done computing
+    //   step kt-1; request step kt+3 into the buffer step kt-1 used; compute step kt.
     // The barrier is the bare instruction (the fence of __syncthreads would wait for all
     // loads in flight); the empty asm statements keep the compiler from moving memory
     // operations across it.  Beyond the last step the descriptors return zeros, never used.
-    constexpr int kLoads = 2 + kXP;
-    constexpr int kWaitOneStepInFlight = (kLoads & 0xF) | (7 << 4) | (15 << 8) | ((kLoads >> 4) << 14);
+    constexpr int kLoads = 2 * (2 + kXP);            // two steps' worth may stay in flight
+    constexpr int kWaitTwoStepsInFlight = (kLoads & 0xF) | (7 << 4) | (15 << 8) | ((kLoads >> 4) << 14);
 #define HGF_STEP(XCUR, WCUR, XFILL, WFILL, KT)                    \
     do {                                                          \
-        __builtin_amdgcn_s_waitcnt(kWaitOneStepInFlight);         \
+        __builtin_amdgcn_s_waitcnt(kWaitTwoStepsInFlight);        \
         asm volatile("" ::: "memory");                            \
         __builtin_amdgcn_s_barrier();                             \
         asm volatile("" ::: "memory");                            \
-        stage(XFILL, WFILL, (KT) + 2);                            \
+        stage(XFILL, WFILL, (KT) + 3);                            \
         __builtin_amdgcn_sched_barrier(0);                        \
         compute(XCUR, WCUR);                                      \
         __builtin_amdgcn_sched_barrier(0);                        \
     } while (0)
 
-    v4u w0[2], w1[2], w2[2];
+    v4u w0[2], w1[2], w2[2], w3[2];
     stage(xs0, w0, 0);
     stage(xs1, w1, 1);
+    stage(xs2, w2, 2);
     int kt = 0;
-    for (; kt + 2 < p.KT; kt += 3) {
-        HGF_STEP(xs0, w0, xs2, w2, kt);
+    for (; kt + 3 < p.KT; kt += 4) {
+        HGF_STEP(xs0, w0, xs3, w3, kt);
         HGF_STEP(xs1, w1, xs0, w0, kt + 1);
         HGF_STEP(xs2, w2, xs1, w1, kt + 2);
+        HGF_STEP(xs3, w3, xs2, w2, kt + 3);
     }
-    if (kt < p.KT) HGF_STEP(xs0, w0, xs2, w2, kt);
+    if (kt < p.KT) HGF_STEP(xs0, w0, xs3, w3, kt);
     if (kt + 1 < p.KT) HGF_STEP(xs1, w1, xs0, w0, kt + 1);
+    if (kt + 2 < p.KT) HGF_STEP(xs2, w2, xs1, w1, kt + 2);
 #undef HGF_STEP
-    __syncthreads();                                 // gs is complete; drains the unused tail loads
+    __syncthreads();                 // gs is complete; every wavefront is done with the activation buffers
 
     // ---- epilogue: correction up-projection on the f16 MFMA, gate, dequantise, store.
     //      Element 4*q + v of an accumulator is row 8*q + 4*hf + v of the row-block, for the
     //      token of the lane.
-    const float s_w = *p.s_w;
-    float sx[kPG];
-    int rs[kPG];
+    // SiLU(A x) of the 128 tokens goes into the (now free) activation buffers, tokens 0..63
+    // into xs0 and 64..127 into xs1, rows of JS*32 bytes with the same XOR permutation of the
+    // 16-byte pieces; the B rows of both row-blocks go to registers.  All of it is requested
+    // in one burst: one memory round trip for the whole epilogue.
+    constexpr int kRowBytes = JS * 32, kPieces = JS * 2, kMask = (kPieces < 8 ? kPieces : 8) - 1;
+    v8h breg[2][JS > 0 ? JS : 1];
+    if (JS > 0) {
+        const rsrc_t hr = make_rsrc(p.h16 + (size_t)m0 * p.hstride, (unsigned)mrows * p.hstride * 2u);
+#pragma unroll
+        for (int buf = 0; buf < 2; ++buf) {
+#pragma unroll
+            for (int i = 0; i < JS / 2; ++i) {
+                const unsigned byte = (unsigned)(4 * i + w) * 1024 + l * 16;
+                const unsigned row = byte / kRowBytes, slot = (byte % kRowBytes) / 16;
+                const unsigned piece = slot ^ (row & kMask);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(hr, (lds_ptr_t)((buf ? xs1 : xs0) + (4 * i + w) * 1024), 16,
+                                                         (int)((buf * 64 + row) * (unsigned)p.hstride * 2u + piece * 16), 0, 0, 0);
+            }
+        }
+        const rsrc_t br = make_rsrc(p.B, (unsigned)p.N * p.rank * 2u);
+        const bool bvec = (p.rank % 8) == 0;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int brow = (rb0 + rb) * kTileRows + jl;
+#pragma unroll
+            for (int js = 0; js < JS; ++js) {
+                const int j0 = js * 16 + hf * 8;
+                breg[rb][js] = bvec ? buf_load8h<true>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N)
+                                    : buf_load8h<false>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N);
+            }
+        }
+        __syncthreads();             // waits for the loads above and makes the staged rows visible
+    }
+    const bool nvec = (p.N % 4) == 0;
+    const int nw0 = rb0 * kTileRows;                 // first of this wavefront's 64 output rows
+    // Coalesced store path: a token's 64 outputs of this wavefront are 128 contiguous bytes of
+    // y.  The fp16 results of 32 tokens at a time are transposed through a wavefront-private
+    // LDS patch (rows of 144 bytes: the 16 spare bytes spread the banks) and leave as 16-byte
+    // stores, eight lanes per token.  Needs the whole 64-row strip in range and 16-byte
+    // aligned rows of y; otherwise (ragged d_out, or the int32 debug output) direct stores.
+    const bool wide = (p.N % 8) == 0 && nw0 + 64 <= p.N && p.acc_debug == nullptr;
+    unsigned char *patch = (w < 2 ? xs2 : xs3) + (w & 1) * 8192;
+    constexpr int kPatchStride = 144;
+
 #pragma unroll
     for (int tg = 0; tg < kPG; ++tg) {
         const int m = m0 + tg * 32 + jl;
-        const bool ok = m < p.M;
-        sx[tg] = ok ? p.s_x[m] : 0.f;
-        rs[tg] = ok ? p.rowsum[m] : 0;
-    }
-    const rsrc_t br = make_rsrc(p.B, p.rank > 0 ? (unsigned)p.N * p.rank * 2u : 0u);
-    const rsrc_t hr = make_rsrc(p.h16, p.rank > 0 ? (unsigned)p.M * p.hstride * 2u : 0u);
-    const bool bvec = (p.rank % 8) == 0;
-    const bool nvec = (p.N % 4) == 0;
+        const float scale = sx[tg] * s_w;
+        v16f corr[2] = {(v16f){}, (v16f){}};
+        if (JS > 0) {
+            const unsigned row = (unsigned)(tg & 1) * 32 + jl;
+            const unsigned char *hrow = ((tg >> 1) ? xs1 : xs0) + row * kRowBytes;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int n0 = (rb0 + rb) * kTileRows;
-        if (n0 >= p.N) break;                        // wavefront-uniform
-        v16f corr[kPG];
+            for (int js = 0; js < JS; ++js) {
+                const unsigned piece = (unsigned)(js * 2 + hf) ^ (row & kMask);
+                const v8h b = *reinterpret_cast<const v8h *>(hrow + piece * 16);
 #pragma unroll
-        for (int tg = 0; tg < kPG; ++tg) corr[tg] = (v16f){};
-        if (p.rank > 0) {
-            const int brow = n0 + jl;
-            for (int js = 0; js < p.hstride / 16; ++js) {
-                const int j0 = js * 16 + hf * 8;
-                const v8h a = bvec ? buf_load8h<true>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N)
-                                   : buf_load8h<false>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N);
-#pragma unroll
-                for (int tg = 0; tg < kPG; ++tg) {
-                    const int m = m0 + tg * 32 + jl;
-                    const v8h b = __builtin_bit_cast(v8h, buf_load16(hr, ((unsigned)m * p.hstride + j0) * 2u, m < p.M));
-                    corr[tg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, corr[tg], 0, 0, 0);
-                }
+                for (int rb = 0; rb < 2; ++rb)
+                    corr[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(breg[rb][js], b, corr[rb], 0, 0, 0);
             }
         }
 #pragma unroll
-        for (int tg = 0; tg < kPG; ++tg) {
-            const int m = m0 + tg * 32 + jl;
-            if (m >= p.M) continue;
-            const float scale = sx[tg] * s_w;
+        for (int rb = 0; rb < 2; ++rb) {
+            const int n0 = nw0 + rb * kTileRows;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int r0 = 8 * q + 4 * hf;
@@ -223,21 +267,36 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     a[v] = acc[rb][tg][4 * q + v] - rs[tg];
-                    o[v] = (_Float16)((float)a[v] * scale + gs[(w * 2 + rb) * kTileRows + r0 + v] * corr[tg][4 * q + v]);
+                    o[v] = (_Float16)((float)a[v] * scale + gs[(w * 2 + rb) * kTileRows + r0 + v] * corr[rb][4 * q + v]);
                 }
-                const size_t at = (size_t)m * p.N + nl;
-                if (nvec && nl + 3 < p.N) {
-                    *reinterpret_cast<v4h *>(p.y + at) = o;
-                    if (p.acc_debug) *reinterpret_cast<v4i *>(p.acc_debug + at) = (v4i){a[0], a[1], a[2], a[3]};
-                } else {
+                if (wide) {
+                    *reinterpret_cast<v4h *>(patch + jl * kPatchStride + (rb * kTileRows + r0) * 2) = o;
+                } else if (m < p.M) {
+                    const size_t at = (size_t)m * p.N + nl;
+                    if (nvec && nl + 3 < p.N) {
+                        *reinterpret_cast<v4h *>(p.y + at) = o;
+                        if (p.acc_debug) *reinterpret_cast<v4i *>(p.acc_debug + at) = (v4i){a[0], a[1], a[2], a[3]};
+                    } else {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        if (nl + v < p.N) {
-                            p.y[at + v] = o[v];
-                            if (p.acc_debug) p.acc_debug[at + v] = a[v];
+                        for (int v = 0; v < 4; ++v) {
+                            if (nl + v < p.N) {
+                                p.y[at + v] = o[v];
+                                if (p.acc_debug) p.acc_debug[at + v] = a[v];
+                            }
                         }
                     }
                 }
+            }
+        }
+        if (wide) {
+            // the patch is private to the wavefront: its own LDS writes are complete once
+            // the read below has been ordered after them (same wavefront, in-order LDS)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int tok = i * 8 + (l >> 3), piece = l & 7;
+                const v4u v = *reinterpret_cast<const v4u *>(patch + tok * kPatchStride + piece * 16);
+                const int mm = m0 + tg * 32 + tok;
+                if (mm < p.M) *reinterpret_cast<v4u *>(p.y + (size_t)mm * p.N + nw0 + piece * 8) = v;
             }
         }
     }
@@ -268,7 +327,13 @@ hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float
     p.hstride = h_stride(L.rank > 0 ? L.rank : 1);
     p.NB = (L.d_out + kPN - 1) / kPN;
     const int MB = (M + kPM - 1) / kPM;
-    hipLaunchKernelGGL(prefill_kernel, dim3(p.NB * MB), dim3(256), 0, st, p);
+    const dim3 grid(p.NB * MB), block(256);
+    switch (L.rank > 0 ? p.hstride / 16 : 0) {
+        case 0: hipLaunchKernelGGL(prefill_kernel<0>, grid, block, 0, st, p); break;
+        case 2: hipLaunchKernelGGL(prefill_kernel<2>, grid, block, 0, st, p); break;
+        case 4: hipLaunchKernelGGL(prefill_kernel<4>, grid, block, 0, st, p); break;
+        default: hipLaunchKernelGGL(prefill_kernel<8>, grid, block, 0, st, p); break;
+    }
     return hipGetLastError();
 }
 
