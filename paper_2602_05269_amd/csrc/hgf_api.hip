@@ -116,7 +116,6 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     dp.rowsum = ws.rowsum;
     dp.M = M;
     dp.G = G;
-    dp.hmode = 0;
     for (int g = 0; g < G; ++g) {
         const hgf_layer &L = layers[g];
         float *slices = reinterpret_cast<float *>(reinterpret_cast<char *>(ws.hslices) + ws.hslices_each * g);
@@ -130,7 +129,6 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
         D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
         D.hpart = slices;
-        D.h16 = nullptr;
         D.y = reinterpret_cast<_Float16 *>(ys[g]);
         D.acc_debug = acc_debug;
         D.N = L.d_out;

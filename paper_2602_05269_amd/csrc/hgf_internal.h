@@ -128,8 +128,7 @@ struct DecLayer {
     const float *s_w;
     const _Float16 *B;
     const _Float16 *alpha;
-    const float *hpart;      // hmode 0: [S, M, hstride] partial sums of A x
-    const _Float16 *h16;     // hmode 1: [M, hstride] SiLU(A x)
+    const float *hpart;      // [S, M, hstride] fp32 partial sums of A x from the prologue
     _Float16 *y;
     int32_t *acc_debug;
     int N, RBn, rank, hstride;
@@ -143,7 +142,7 @@ struct DecodeParams {
     int wg_start[kMaxGroup + 1];
     int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4 or 8)
     int CT, xstride;         // tiles of d_in staged in LDS at a time; bytes per staged row
-    int S, hmode;            // slices of the correction partial sums; see DecLayer
+    int S;                   // slices of the correction partial sums
     int h_off, g_off;        // byte offsets in LDS of the SiLU(A x) rows and of the tanh(alpha) table
 };
 
