@@ -17,8 +17,7 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
         off += align256(bytes);
         return r;
     };
-    ws.acc = reinterpret_cast<int32_t *>(take(kAccZeroBytes));
-    ws.counters = reinterpret_cast<int32_t *>(take(size_t(kNumCounters) * 4));
+    ws.flags = reinterpret_cast<int32_t *>(take(kZeroBytes));
     const int Kp = round_up(d_in, kTileCols);
     ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
@@ -101,6 +100,34 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
                             int32_t *acc_debug, const Workspace &ws, hipStream_t st)
 {
     const int K = layers[0].d_in;
+    bool fused = M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
+    for (int g = 0; g < G; ++g) fused = fused && (layers[g].rank == 0 || aligned16(layers[g].A_f16));
+    if (fused) {
+        FusedParams fp;
+        fp.x = reinterpret_cast<const _Float16 *>(x);
+        fp.M = M;
+        fp.K = K;
+        fp.G = G;
+        fp.flags = ws.flags;
+        for (int g = 0; g < G; ++g) {
+            const hgf_layer &L = layers[g];
+            DecLayer &D = fp.L[g];
+            D.packed = reinterpret_cast<const v4u *>(L.W_packed);
+            D.s_w = L.s_w;
+            D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
+            D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
+            D.hpart = reinterpret_cast<float *>(reinterpret_cast<char *>(ws.hslices) + ws.hslices_each * g);
+            D.y = reinterpret_cast<_Float16 *>(ys[g]);
+            D.acc_debug = acc_debug;
+            D.N = L.d_out;
+            D.RBn = round_up(L.d_out, kTileRows) / kTileRows;
+            D.rank = L.rank;
+            D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
+            fp.A[g] = reinterpret_cast<const _Float16 *>(L.A_f16);
+        }
+        ProfileScope prof(0, st);
+        return from_hip(launch_fused(fp, st));
+    }
     ProParams pp;
     pp.x = reinterpret_cast<const _Float16 *>(x);
     pp.xq = ws.xq;
@@ -199,9 +226,8 @@ hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *str
 {
     if (!workspace) return HGF_ERR_NULL;
     if (!aligned16(workspace)) return HGF_ERR_ALIGN;
-    if (workspace_bytes < align256(kAccZeroBytes) + align256(size_t(kNumCounters) * 4)) return HGF_ERR_WORKSPACE;
-    return from_hip(launch_fill_zero(workspace, align256(kAccZeroBytes) + align256(size_t(kNumCounters) * 4),
-                                     reinterpret_cast<hipStream_t>(stream)));
+    if (workspace_bytes < align256(kZeroBytes)) return HGF_ERR_WORKSPACE;
+    return from_hip(launch_fill_zero(workspace, align256(kZeroBytes), reinterpret_cast<hipStream_t>(stream)));
 }
 
 hgf_status hgf_quantize_pack_weights(const float *W, int d_out, int d_in, void *packed_out, float *s_w_out,

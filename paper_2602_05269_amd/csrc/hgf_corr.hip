@@ -26,8 +26,6 @@ struct CorrParams {
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
-__device__ inline float silu(float h) { return h / (1.0f + expf(-h)); }
-
 // Staged rows are permuted in units of 16 bytes by XOR with (row mod 8), so that the lanes
 // reading the same piece of consecutive rows spread over the banks.
 __device__ inline unsigned slot_of(unsigned piece, unsigned row) { return piece ^ (row & 7u); }

@@ -24,18 +24,6 @@ namespace hgf {
 
 namespace {
 
-__device__ inline v4i widen_codes(uint32_t w)
-{
-    v4i a;
-    a[0] = (int)(w & 0x03030303u);
-    a[1] = (int)((w >> 2) & 0x03030303u);
-    a[2] = (int)((w >> 4) & 0x03030303u);
-    a[3] = (int)((w >> 6) & 0x03030303u);
-    return a;
-}
-
-__device__ inline float silu(float h) { return h / (1.0f + expf(-h)); }
-
 #ifndef HGF_PF1
 #define HGF_PF1 8
 #endif
@@ -309,6 +297,7 @@ constexpr int kDecodeLdsBudget = 64 * 1024;
 }  // namespace
 
 void set_decode_target_wgs(int v) { g_target_waves = v > 0 ? v : 2048; }
+int decode_target_waves() { return g_target_waves; }
 
 // Fills in the launch shape of a group whose layers, activations and outputs are set.
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)

@@ -65,21 +65,62 @@ __device__ inline v8h buf_load8h(rsrc_t r, unsigned elem, int cols_left, bool ok
     return v;
 }
 
+// Same, visible to every compute unit of the device: partial results that one workgroup
+// writes and another reads within a single launch bypass the per-XCD L2 (sc1).
+__device__ inline unsigned buf_load4_agent(rsrc_t r, unsigned off, bool ok = true)
+{
+    return (unsigned)__builtin_amdgcn_raw_buffer_load_b32(r, (int)(ok ? off : kOob), 0, 16);
+}
+__device__ inline void buf_store16_agent(rsrc_t r, unsigned off, v4f v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)off, 0, 16);
+}
+
+// ---- arithmetic shared by the kernels ---------------------------------------------------
+// Four bytes of 2-bit codes (T+1) -> the four int8 operand registers of one MFMA.
+__device__ inline v4i widen_codes(uint32_t w)
+{
+    v4i a;
+    a[0] = (int)(w & 0x03030303u);
+    a[1] = (int)((w >> 2) & 0x03030303u);
+    a[2] = (int)((w >> 4) & 0x03030303u);
+    a[3] = (int)((w >> 6) & 0x03030303u);
+    return a;
+}
+__device__ inline float silu(float h) { return h / (1.0f + expf(-h)); }
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline int wave_sum(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+// Sec. 2.2.1 activation quantiser: round half to even, clip to [-127, 127].
+__device__ inline int quant1(float x, float inv)
+{
+    float q = rintf(x * inv);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 // ---- workspace layout -------------------------------------------------------------
-// [ zero region: split-K int32 accumulators | arrival counters ]  (zero between calls)
-// [ x_q | s_x | rowsum | h16 | h partials | weight-quantiser partial sums ]
-constexpr size_t kAccZeroBytes = size_t(64) * 32768 * 4;   // 8 MiB of int32 accumulators
-constexpr int kNumCounters = 16384;                        // int32 arrival counters
-constexpr size_t kZeroBytes = kAccZeroBytes + size_t(kNumCounters) * 4;
+// [ flags (zero between calls) | x_q | s_x | rowsum | h16 | h partials | weight-quantiser sums ]
+constexpr int kNumFlags = 64;                              // int32 words the kernels leave zero
+constexpr size_t kZeroBytes = size_t(kNumFlags) * 4;
 constexpr int kWsumBlocks = 1024;                          // fp64 partial sums of |W|
 constexpr int kMaxHSplit = 32;                             // k-splits of the rank-r down-projection
 
 struct Workspace {
-    int32_t *acc;        // zero region
-    int32_t *counters;   // zero region: [0, 8192) decode row-blocks, [8192, 16384) h tiles
+    int32_t *flags;      // zero region: [0] correction workgroups done, [1] decode workgroups done,
+                         // [2] sticky: a bounded wait ran out
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
@@ -146,6 +187,24 @@ struct DecodeParams {
     int h_off, g_off;        // byte offsets in LDS of the SiLU(A x) rows and of the tanh(alpha) table
 };
 
+// Fused launch for a handful of tokens: the leading workgroups compute the partial sums of
+// A x, the others quantise the tokens themselves and run the decode path.
+constexpr int kMaxFusedM = 4;
+constexpr int kMaxFusedK = 12288;
+struct FusedParams {
+    const _Float16 *x;            // [M, K] fp16
+    int M, K, Kp, KT, G;
+    DecLayer L[kMaxGroup];        // hpart: [S, M, hstride], written and read inside the launch
+    const _Float16 *A[kMaxGroup];
+    int wg_start[kMaxGroup + 1];  // decode workgroups, counted from the first of them
+    int job_start[kMaxGroup + 1]; // wavefront jobs of the correction workgroups
+    int ncorr;                    // leading workgroups that compute A x
+    int RW, KW;
+    int S, pairs, pairs_per_slice;
+    int xstride, h_off, g_off;    // LDS: bytes per staged token row; offsets of SiLU(A x) and tanh(alpha)
+    int32_t *flags;
+};
+
 // ---- kernel launchers (each validates nothing: the ABI layer has done it) -----------
 hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_out, hipStream_t st);
 hipError_t launch_pack(const float *W, int N, int K, const float *s_w, uint32_t *packed, hipStream_t st);
@@ -158,6 +217,8 @@ hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, 
 int prologue_slices(int M, int K);
 hipError_t launch_prologue(ProParams &p, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
+hipError_t launch_fused(FusedParams &p, hipStream_t st);
+int decode_target_waves();
 void set_decode_target_wgs(int v);
 hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
                           hipStream_t st);

@@ -40,16 +40,6 @@ struct PrefillParams {
     int NB;                        // workgroups along the output rows
 };
 
-__device__ inline v4i widen_codes(uint32_t w)
-{
-    v4i a;
-    a[0] = (int)(w & 0x03030303u);
-    a[1] = (int)((w >> 2) & 0x03030303u);
-    a[2] = (int)((w >> 4) & 0x03030303u);
-    a[3] = (int)((w >> 6) & 0x03030303u);
-    return a;
-}
-
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 // LDS image of a kPM x 128 activation tile: row r at byte 128*r, its eight 16-byte pieces

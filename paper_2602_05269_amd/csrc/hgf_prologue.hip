@@ -15,27 +15,6 @@ namespace hgf {
 
 namespace {
 
-__device__ inline float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
-__device__ inline int wave_sum(int v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-__device__ inline int quant1(float x, float inv)
-{
-    float q = rintf(x * inv);
-    q = fminf(fmaxf(q, -127.0f), 127.0f);
-    return (int)q;
-}
-
 constexpr int kRegVecs = 6;   // a token row of up to 6*256*8 = 12288 columns stays in registers
 
 // One workgroup quantises one token row.  VEC: d_in % 8 == 0 (16-byte loads).

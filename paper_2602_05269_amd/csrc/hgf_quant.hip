@@ -12,27 +12,6 @@ namespace hgf {
 
 namespace {
 
-__device__ inline float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
-__device__ inline int wave_sum(int v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-__device__ inline int quant1(float x, float inv)
-{
-    float q = rintf(x * inv);
-    q = fminf(fmaxf(q, -127.0f), 127.0f);
-    return (int)q;
-}
-
 template <bool VEC>
 __global__ __launch_bounds__(256) void quantize_kernel(const _Float16 *__restrict__ x, int K, int Kp,
                                                        int8_t *__restrict__ xq, float *__restrict__ s_x,

@@ -81,6 +81,21 @@ def test_decode_shapes_parity(M, K, N, r, ws):
     g.check_forward(c["x"])
 
 
+@pytest.mark.parametrize("M,K,N,r", [
+    (1, 8, 1, 1), (1, 128, 32, 16), (1, 4096, 1000, 64), (2, 4104, 96, 20), (3, 1024, 33, 128), (4, 12288, 160, 64),
+    (4, 11008, 64, 128), (1, 3072, 3072, 32), (2, 768, 2304, 0), (4, 8, 130, 7), (1, 12288, 31, 128),
+])
+def test_few_token_single_launch_parity(M, K, N, r, ws):
+    """M <= 4 with 16-byte rows takes the single-launch path: tokens quantised inside the
+    decode workgroups, correction partial sums handed over within the launch.  Its counters
+    in the workspace are zero again afterwards and no wait ran out."""
+    c = synth.make_custom(3000 + M + K + N + r, M, K, N, max(r, 1), act="student_t3")
+    g = GpuLayer(c, ws, rank0=(r == 0))
+    for _ in range(2):
+        g.check_forward(c["x"])
+        assert not ws.buf[:256].view(torch.int32).any().item()
+
+
 @pytest.mark.parametrize("M,K,N,r", [(65, 256, 128, 16), (130, 512, 200, 32), (256, 1365, 256, 64)])
 def test_large_m_parity(M, K, N, r, ws):
     c = synth.make_custom(2000 + M + K + N + r, M, K, N, r, act="student_t4")
