@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.hgf_stack_forward.argtypes = [ctypes.POINTER(hgf_layer), ci, ctypes.POINTER(vp), ci, ci, vp, sz, vp]
     L.hgf_set_decode_target_workgroups.restype = None
     L.hgf_set_decode_target_workgroups.argtypes = [ci]
+    L.hgf_set_single_launch.restype = None
+    L.hgf_set_single_launch.argtypes = [ci]
     L.hgf_profile_enable.restype = None
     L.hgf_profile_enable.argtypes = [ci]
     L.hgf_profile_collect.restype = ci
@@ -127,6 +129,10 @@ class Workspace:
 
 def hgf_workspace_init(ws: Workspace, stream=None) -> None:
     _check(lib().hgf_workspace_init(ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_workspace_init")
+
+
+def hgf_set_single_launch(on: bool) -> None:
+    lib().hgf_set_single_launch(1 if on else 0)
 
 
 def hgf_set_decode_target_workgroups(n: int) -> None:

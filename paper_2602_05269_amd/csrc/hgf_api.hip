@@ -18,6 +18,7 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
         return r;
     };
     ws.flags = reinterpret_cast<int32_t *>(take(kZeroBytes));
+    ws.mail = reinterpret_cast<unsigned char *>(take(2 * kMailBytes));
     const int Kp = round_up(d_in, kTileCols);
     ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
@@ -58,6 +59,7 @@ hgf_status from_hip(hipError_t e) { return e == hipSuccess ? HGF_OK : HGF_ERR_DE
 
 // Profiling aid: event pairs recorded around main-kernel launches, by kind (0 decode, 1 prefill).
 bool g_profile = false;
+bool g_single_launch = true;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events[2];
 std::vector<hipEvent_t> g_event_pool;
 
@@ -100,8 +102,11 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
                             int32_t *acc_debug, const Workspace &ws, hipStream_t st)
 {
     const int K = layers[0].d_in;
-    bool fused = M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
-    for (int g = 0; g < G; ++g) fused = fused && (layers[g].rank == 0 || aligned16(layers[g].A_f16));
+    bool fused = g_single_launch && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
+    for (int g = 0; g < G; ++g)
+        fused = fused && (layers[g].rank == 0 ||
+                          (layers[g].rank % 8 == 0 && aligned16(layers[g].A_f16) && aligned16(layers[g].B_f16) &&
+                           (reinterpret_cast<uintptr_t>(layers[g].alpha_f16) & 3u) == 0));
     if (fused) {
         FusedParams fp;
         fp.x = reinterpret_cast<const _Float16 *>(x);
@@ -109,6 +114,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         fp.K = K;
         fp.G = G;
         fp.flags = ws.flags;
+        fp.mail = ws.mail;
         for (int g = 0; g < G; ++g) {
             const hgf_layer &L = layers[g];
             DecLayer &D = fp.L[g];
@@ -116,7 +122,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
             D.s_w = L.s_w;
             D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
             D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-            D.hpart = reinterpret_cast<float *>(reinterpret_cast<char *>(ws.hslices) + ws.hslices_each * g);
+            D.hpart = nullptr;
             D.y = reinterpret_cast<_Float16 *>(ys[g]);
             D.acc_debug = acc_debug;
             D.N = L.d_out;
@@ -125,8 +131,11 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
             D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
             fp.A[g] = reinterpret_cast<const _Float16 *>(L.A_f16);
         }
-        ProfileScope prof(0, st);
-        return from_hip(launch_fused(fp, st));
+        size_t lds_bytes = 0;
+        if (plan_fused(fp, &lds_bytes)) {
+            ProfileScope prof(0, st);
+            return from_hip(launch_fused(fp, lds_bytes, st));
+        }
     }
     ProParams pp;
     pp.x = reinterpret_cast<const _Float16 *>(x);
@@ -226,8 +235,11 @@ hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *str
 {
     if (!workspace) return HGF_ERR_NULL;
     if (!aligned16(workspace)) return HGF_ERR_ALIGN;
-    if (workspace_bytes < align256(kZeroBytes)) return HGF_ERR_WORKSPACE;
-    return from_hip(launch_fill_zero(workspace, align256(kZeroBytes), reinterpret_cast<hipStream_t>(stream)));
+    const Workspace ws = carve_workspace(workspace, 1, 1, 1, 0);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (launch_fill(ws.flags, align256(kZeroBytes), 0u, st) != hipSuccess) return HGF_ERR_DEVICE;
+    return from_hip(launch_fill(ws.mail, 2 * kMailBytes, 0xFFFFFFFFu, st));
 }
 
 hgf_status hgf_quantize_pack_weights(const float *W, int d_out, int d_in, void *packed_out, float *s_w_out,
@@ -362,5 +374,7 @@ hgf_status hgf_profile_collect(double *ms_out, long long *launches_out)
 
 /* Tuning hook for benchmarks: target number of decode workgroups per launch (0 = default). */
 void hgf_set_decode_target_workgroups(int n) { set_decode_target_wgs(n); }
+
+void hgf_set_single_launch(int on) { g_single_launch = on != 0; }
 
 }  // extern "C"

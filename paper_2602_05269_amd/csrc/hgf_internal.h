@@ -112,8 +112,10 @@ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 // ---- workspace layout -------------------------------------------------------------
-// [ flags (zero between calls) | x_q | s_x | rowsum | h16 | h partials | weight-quantiser sums ]
-constexpr int kNumFlags = 64;                              // int32 words the kernels leave zero
+// [ flags | exchange buffers of the single-launch path | x_q | s_x | rowsum | h16 | h partials |
+//   weight-quantiser sums ]   (hgf_workspace_init zeroes the flags and fills the exchange
+//   buffers with the sentinel pattern)
+constexpr int kNumFlags = 64;                              // int32 words: launch counter, arrival count, sticky error
 constexpr size_t kZeroBytes = size_t(kNumFlags) * 4;
 constexpr int kWsumBlocks = 1024;                          // fp64 partial sums of |W|
 constexpr int kMaxHSplit = 32;                             // k-splits of the rank-r down-projection
@@ -121,6 +123,7 @@ constexpr int kMaxHSplit = 32;                             // k-splits of the ra
 struct Workspace {
     int32_t *flags;      // zero region: [0] correction workgroups done, [1] decode workgroups done,
                          // [2] sticky: a bounded wait ran out
+    unsigned char *mail; // two exchange buffers of kMailBytes, sentinel-filled between launches
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
@@ -155,6 +158,7 @@ struct ProLayer {
 };
 struct ProParams {
     const _Float16 *x;
+    unsigned char *mail; // two exchange buffers of kMailBytes, sentinel-filled between launches
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
@@ -187,29 +191,34 @@ struct DecodeParams {
     int h_off, g_off;        // byte offsets in LDS of the SiLU(A x) rows and of the tanh(alpha) table
 };
 
-// Fused launch for a handful of tokens: the leading workgroups compute the partial sums of
-// A x, the others quantise the tokens themselves and run the decode path.
+// Single persistent launch for a handful of tokens: every workgroup quantises the tokens
+// itself, streams its share of the row-blocks ("units") and exchanges the partial sums of
+// A x with the others through a sentinel-filled buffer in the workspace.
 constexpr int kMaxFusedM = 4;
 constexpr int kMaxFusedK = 12288;
+constexpr int kFusedSplit = 24;                               // slices of d_in at most (512 columns each)
+constexpr size_t kMailLayerBytes = size_t(64) * HGF_MAX_RANK * 4;   // 64 (slice, token) rows of fp32 per layer
+constexpr size_t kMailBytes = kMailLayerBytes * kMaxGroup;    // one exchange buffer; the workspace holds two
 struct FusedParams {
     const _Float16 *x;            // [M, K] fp16
-    int M, K, Kp, KT, G;
-    DecLayer L[kMaxGroup];        // hpart: [S, M, hstride], written and read inside the launch
+    int M, K, Kp, KT, TPW, G;     // TPW: tiles of a unit per streaming wavefront
+    DecLayer L[kMaxGroup];        // hpart unused
     const _Float16 *A[kMaxGroup];
-    int wg_start[kMaxGroup + 1];  // decode workgroups, counted from the first of them
-    int job_start[kMaxGroup + 1]; // wavefront jobs of the correction workgroups
-    int ncorr;                    // leading workgroups that compute A x
-    int RW, KW;
+    int ustart[kMaxGroup + 1];    // running sum of the layers' row-blocks
+    int job_start[kMaxGroup + 1]; // running sum of the layers' (rank tile, slice) jobs
+    int nwg;                      // workgroups of the launch
     int S, pairs, pairs_per_slice;
-    int xstride, h_off, g_off;    // LDS: bytes per staged token row; offsets of SiLU(A x) and tanh(alpha)
-    int32_t *flags;
+    int xstride, tile_off, h_off; // LDS: bytes per quantised token row; offsets of the units' int32 sums and of SiLU(A x)
+    int unit_off, unit_stride, unit_alpha;   // LDS: staged epilogue operands (B rows, alpha) per unit
+    unsigned char *mail;          // two exchange buffers of kMailBytes
+    int32_t *flags;               // [0] launch counter, [1] workgroups done, [2] sticky: a wait ran out
 };
 
 // ---- kernel launchers (each validates nothing: the ABI layer has done it) -----------
 hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_out, hipStream_t st);
 hipError_t launch_pack(const float *W, int N, int K, const float *s_w, uint32_t *packed, hipStream_t st);
 hipError_t launch_unpack(const uint32_t *packed, int N, int K, int8_t *T, hipStream_t st);
-hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
+hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st);
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st);
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, int rank,
@@ -217,7 +226,8 @@ hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, 
 int prologue_slices(int M, int K);
 hipError_t launch_prologue(ProParams &p, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
-hipError_t launch_fused(FusedParams &p, hipStream_t st);
+bool plan_fused(FusedParams &p, size_t *lds_bytes);
+hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);
 int decode_target_waves();
 void set_decode_target_wgs(int v);
 hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,

@@ -112,11 +112,11 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *__restrict_
     }
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint4 *__restrict__ p, size_t n16)
+__global__ __launch_bounds__(256) void fill_kernel(uint4 *__restrict__ p, size_t n16, uint32_t word)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+    for (; i < n16; i += stride) p[i] = make_uint4(word, word, word, word);
 }
 
 }  // namespace
@@ -146,13 +146,13 @@ hipError_t launch_unpack(const uint32_t *packed, int N, int K, int8_t *T, hipStr
     return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st)
+hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st)
 {
     const size_t n16 = bytes / 16;                               // callers pass multiples of 16
     unsigned blocks = (unsigned)((n16 + 255) / 256);
     if (blocks > 4096) blocks = 4096;
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, (uint4 *)p, n16);
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks), dim3(256), 0, st, (uint4 *)p, n16, word);
     return hipGetLastError();
 }
 

@@ -86,14 +86,27 @@ def test_decode_shapes_parity(M, K, N, r, ws):
     (4, 11008, 64, 128), (1, 3072, 3072, 32), (2, 768, 2304, 0), (4, 8, 130, 7), (1, 12288, 31, 128),
 ])
 def test_few_token_single_launch_parity(M, K, N, r, ws):
-    """M <= 4 with 16-byte rows takes the single-launch path: tokens quantised inside the
-    decode workgroups, correction partial sums handed over within the launch.  Its counters
-    in the workspace are zero again afterwards and no wait ran out."""
+    """M <= 4 with 16-byte rows takes the single persistent launch: tokens quantised inside
+    the workgroups, partial sums of A x exchanged within the launch.  Afterwards the launch
+    counter in the workspace has advanced by one, the arrival count is back at zero and no
+    wait has run out; the two-launch path gives the same integers.  (Ranks that are not
+    multiples of 8 have unaligned rows of B and take the two-launch path to begin with.)"""
     c = synth.make_custom(3000 + M + K + N + r, M, K, N, max(r, 1), act="student_t3")
     g = GpuLayer(c, ws, rank0=(r == 0))
-    for _ in range(2):
-        g.check_forward(c["x"])
-        assert not ws.buf[:256].view(torch.int32).any().item()
+    flags = lambda: ws.buf[:12].view(torch.int32).cpu().numpy().copy()
+    for _ in range(3):
+        before = flags()
+        y1, _ = g.check_forward(c["x"])
+        after = flags()
+        assert after[0] == before[0] + (1 if r % 8 == 0 else 0) and after[1] == 0 and after[2] == 0, (before, after)
+    hb.hgf_set_single_launch(False)
+    try:
+        before = flags()
+        y2, _ = g.check_forward(c["x"])
+        assert np.array_equal(flags(), before)
+    finally:
+        hb.hgf_set_single_launch(True)
+    assert_close_fp16(y1, y2.astype(np.float64))
 
 
 @pytest.mark.parametrize("M,K,N,r", [(65, 256, 128, 16), (130, 512, 200, 32), (256, 1365, 256, 64)])
