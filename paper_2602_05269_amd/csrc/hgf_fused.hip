@@ -336,7 +336,21 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
     unsigned char *mine = p.mail + (size_t)(epoch & 1u) * kMailBytes;
     unsigned char *other = p.mail + (size_t)((epoch & 1u) ^ 1u) * kMailBytes;
 
-    // ---- first slice of A x: request its operands; then the epilogue operands of every unit
+    {   // the units' [token][row] sums start at zero (before any LDS-direct load: an LDS access
+        // behind one makes the compiler wait for it)
+        int *tiles = reinterpret_cast<int *>(lds + p.tile_off);
+        for (int e = l; e < nunits * kMaxFusedM * kTileRows; e += 64) tiles[e] = 0;
+    }
+    // ---- requests, all up front: the epilogue operands of every unit (LDS-direct; issued first
+    //      because the compiler drains the queue before a loop of such loads), the layers'
+    //      weight scales (four guarded loads; absent layers read zero), then the operands of
+    //      the first slice of A x
+    unsigned char *ustage = lds + p.unit_off;
+    for (int i = 0; i < nunits; ++i) stage_unit(p, ustage + i * p.unit_stride, c + i * p.nwg);
+    const unsigned swb0 = buf_load4(make_rsrc(p.L[0].s_w, nunits > 0 ? 4u : 0u), 0u);
+    const unsigned swb1 = buf_load4(make_rsrc(p.L[1].s_w, nunits > 0 && p.G > 1 ? 4u : 0u), 0u);
+    const unsigned swb2 = buf_load4(make_rsrc(p.L[2].s_w, nunits > 0 && p.G > 2 ? 4u : 0u), 0u);
+    const unsigned swb3 = buf_load4(make_rsrc(p.L[3].s_w, nunits > 0 && p.G > 3 ? 4u : 0u), 0u);
     int job = p.nwg - 1 - c;            // the highest workgroups, which own the fewest units, come first
     JobRegs jr;
     int g = 0, rt = 0, sp = 0, kp0 = 0, kp1 = 0;
@@ -346,24 +360,20 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
         kp1 = min(kp0 + p.pairs_per_slice, p.pairs);
         job_load(p, jr, g, rt, kp0, kp1);
     }
-    unsigned char *ustage = lds + p.unit_off;
-    for (int i = 0; i < nunits; ++i) stage_unit(p, ustage + i * p.unit_stride, c + i * p.nwg);
-    {   // the units' [token][row] sums start at zero
-        int *tiles = reinterpret_cast<int *>(lds + p.tile_off);
-        for (int e = l; e < nunits * kMaxFusedM * kTileRows; e += 64) tiles[e] = 0;
-    }
-
     // The quantiser's barriers.  Bare barriers: this wavefront shares no data with the others
     // at them (a fence would make it wait for everything it has just requested); only the
     // zeroed control words must have landed.  Its slice of A x goes between the first two, in
     // the time the others spend quantising.
-    auto run_job = [&]() {
+    auto job_compute = [&]() {
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         acc = job_mfma(jr, acc);
         for (int kpb = kp0 + kUN; kpb < kp1; kpb += kUN) {
             job_load(p, jr, g, rt, kpb, kp1);
             acc = job_mfma(jr, acc);
         }
+        return acc;
+    };
+    auto job_store = [&](v4f acc) {
         // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of layer g
         const int i = l & 15, kb = l >> 4, hstride = p.L[g].hstride;
         const rsrc_t hr = make_rsrc(mine + (size_t)g * kMailLayerBytes, (unsigned)kMailLayerBytes);
@@ -375,9 +385,19 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     }
-    if (job < njobs) {
-        run_job();
-        job += p.nwg;
+    {
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        if (job < njobs) acc = job_compute();
+        // A read of the staged operands, placed where it costs nothing: the compiler orders it
+        // behind the LDS-direct loads, and these have landed once the job's operands (requested
+        // after them) are here.  Without it the first LDS access further down would wait for
+        // every outstanding memory operation -- the store below included, whose
+        // acknowledgement takes microseconds while the weight stream saturates the memory.
+        asm volatile("" ::"v"(*reinterpret_cast<volatile int *>(lds + p.unit_off)) : "memory");
+        if (job < njobs) {
+            job_store(acc);
+            job += p.nwg;
+        }
     }
     if (nunits > 0) {
         for (int b = 1; b < 2 * p.M; ++b) {
@@ -391,23 +411,22 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
         kp0 = sp * p.pairs_per_slice;
         kp1 = min(kp0 + p.pairs_per_slice, p.pairs);
         job_load(p, jr, g, rt, kp0, kp1);
-        run_job();
+        job_store(job_compute());
         job += p.nwg;
     }
-    {   // my share of the sentinels the next launch expects to find in the other buffer
+    // ---- my share of the sentinels the next launch expects to find in the other buffer.
+    //      Placed where nothing waits for the stores: behind the first LDS access that follows
+    //      the LDS-direct loads (the compiler makes that access wait for every outstanding
+    //      memory operation, stores included), and well before the end of the launch.
+    auto fill_other = [&]() {
         const rsrc_t orr = make_rsrc(other, (unsigned)kMailBytes);
         const v4f s4 = __builtin_bit_cast(v4f, (v4u){kSentinel, kSentinel, kSentinel, kSentinel});
         for (unsigned v = (unsigned)c * 64u + l; v < (unsigned)(kMailBytes / 16); v += (unsigned)p.nwg * 64u)
             buf_store16_agent(orr, v * 16u, s4);
-    }
+    };
+    if (nunits == 0) fill_other();
 
     if (nunits > 0) {
-        // the layers' weight scales: four guarded loads in flight together (absent layers read zero)
-        const unsigned swb0 = buf_load4(make_rsrc(p.L[0].s_w, 4u), 0u);
-        const unsigned swb1 = buf_load4(make_rsrc(p.L[1].s_w, p.G > 1 ? 4u : 0u), 0u);
-        const unsigned swb2 = buf_load4(make_rsrc(p.L[2].s_w, p.G > 2 ? 4u : 0u), 0u);
-        const unsigned swb3 = buf_load4(make_rsrc(p.L[3].s_w, p.G > 3 ? 4u : 0u), 0u);
-
         // ---- collect every slice: h[g][m][j] = SiLU(sum_sp partial) (step 6).  A lane takes four
         //      consecutive ranks of one (layer, token); the layers of the group are laid end to
         //      end so that a single batch of loads -- one round trip -- usually covers them all.
@@ -467,11 +486,25 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
         // ---- per unit: lane n < 32 owns output row n of the unit for every token
         const int *tiles = reinterpret_cast<const int *>(lds + p.tile_off);
         const _Float16 bad = __builtin_bit_cast(_Float16, (unsigned short)0x7e00);
+        fill_other();
+        // the layers' output descriptions in scalar registers: the loop selects, it never loads
+        _Float16 *const y0 = p.L[0].y, *const y1 = p.L[1].y, *const y2 = p.L[2].y, *const y3 = p.L[3].y;
+        int32_t *const d0 = p.L[0].acc_debug, *const d1 = p.L[1].acc_debug, *const d2 = p.L[2].acc_debug,
+                       *const d3 = p.L[3].acc_debug;
+        const int N0 = p.L[0].N, N1 = p.L[1].N, N2 = p.L[2].N, N3 = p.L[3].N;
+        const int us1 = p.G > 1 ? p.ustart[1] : 0x7fffffff, us2 = p.G > 2 ? p.ustart[2] : 0x7fffffff,
+                  us3 = p.G > 3 ? p.ustart[3] : 0x7fffffff;
         for (int i = 0; i < nunits; ++i) {
             const unsigned char *op = ustage + i * p.unit_stride;
-            const int u = c + i * p.nwg, gg = layer_of(p, u);
-            const DecLayer &L = p.L[gg];
-            const int n0 = (u - p.ustart[gg]) * kTileRows;
+            const int u = c + i * p.nwg;
+            int gg = 0, ufirst = 0, LN = N0, Lrank = rk0, Lhstride = hs0;
+            _Float16 *Ly = y0;
+            int32_t *Ldbg = d0;
+            unsigned swb = swb0;
+            if (u >= us1) { gg = 1; ufirst = us1; LN = N1; Lrank = rk1; Lhstride = hs1; Ly = y1; Ldbg = d1; swb = swb1; }
+            if (u >= us2) { gg = 2; ufirst = us2; LN = N2; Lrank = rk2; Lhstride = hs2; Ly = y2; Ldbg = d2; swb = swb2; }
+            if (u >= us3) { gg = 3; ufirst = us3; LN = N3; Lrank = rk3; Lhstride = hs3; Ly = y3; Ldbg = d3; swb = swb3; }
+            const int n0 = (u - ufirst) * kTileRows;
             int polls = 0;
             while (!failed && lds_load(&ctl->arrived[i]) < kStream) {
                 if (++polls >= kLdsPolls) {
@@ -484,19 +517,18 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
             // corr[m] of lane n: sum_j h[m][j] B[n0+n][j]  (tokens as matrix rows, as in the streaming side)
             v16f corr = (v16f){};
             float gate = 0.f;
-            if (L.rank > 0) {
+            if (Lrank > 0) {
                 gate = tanh_fast((float)*reinterpret_cast<const _Float16 *>(op + p.unit_alpha + jl * 2));
                 const _Float16 *hrow = hs + (gg * p.M + jl) * kHsStride + hf * 8;
                 const unsigned char *brow = op + (hf * 32 + jl) * 16;
-                switch (L.hstride / 16) {
+                switch (Lhstride / 16) {
                     case 2: corr = corr_unit<2>(hrow, brow, jl < p.M); break;
                     case 4: corr = corr_unit<4>(hrow, brow, jl < p.M); break;
                     default: corr = corr_unit<8>(hrow, brow, jl < p.M); break;
                 }
             }
             const int n = n0 + l;
-            if (l < 32 && n < L.N) {
-                const unsigned swb = gg == 0 ? swb0 : (gg == 1 ? swb1 : (gg == 2 ? swb2 : swb3));
+            if (l < 32 && n < LN) {
                 const float s_w = __builtin_bit_cast(float, swb);
 #pragma unroll
                 for (int m = 0; m < kMaxFusedM; ++m) {
@@ -504,8 +536,8 @@ __device__ __forceinline__ void service_wave(const FusedParams &p, unsigned char
                         const int a = tiles[(i * kMaxFusedM + m) * kTileRows + l] - sh_rs[m];
                         _Float16 o = (_Float16)((float)a * (sh_sx[m] * s_w) + gate * corr[m]);
                         if (failed) o = bad;
-                        L.y[(size_t)m * L.N + n] = o;
-                        if (L.acc_debug) L.acc_debug[(size_t)m * L.N + n] = a;
+                        Ly[(size_t)m * LN + n] = o;
+                        if (Ldbg) Ldbg[(size_t)m * LN + n] = a;
                     }
                 }
             }
