@@ -9,10 +9,15 @@ Default workload: the 7B-shape FFN decode at M=1 (up, gate: 4096->11008; down:
 11008->4096; r=128) over 32 distinct weight instances chained block to block, 1.46 GB of
 parameters per step, so every step streams its weights from HBM (nothing fits in cache).
 `value` is the achieved HBM GB/s over the algorithmic bytes of the step.  The same JSON
-line also carries: tokens/s, the roofline record of the main decode kernel (its duration
-measured with HIP events on the launch stream in a second pass), the CPU oracle timed on
-a bounded sample, and secondary cases (the 8-layer d=512 stack at M=1, the 1.2B-shape
-layer at M=1, the 3B-shape prefill layer at M=2048).
+line also carries: tokens/s, the roofline record of the decode kernel (one persistent
+launch per group of layers: up+gate, then down; its duration measured with HIP events on
+the launch stream in a second pass; its HBM traffic from the committed counter summary
+under profiles/), the CPU oracle timed on a bounded sample, and secondary cases (the
+8-layer d=512 stack at M=1, the 1.2B-shape layer at M=1, the 3B-shape prefill layer at
+M=2048).
+
+`--copy-probe MIB` instead runs a plain elementwise copy of that many MiB a few times:
+the kernel of known size against which the HBM counters are scaled.
 """
 from __future__ import annotations
 
@@ -83,16 +88,22 @@ class Workload:
         self.param_bytes = sum(K * N / 4 + 2 * r * (K + N) + 2 * N + 4 for K, N, r in self.shapes)
 
 
-def time_steps(fn, steps: int, warmup: int) -> float:
-    """Seconds per step: `warmup` untimed calls, then exactly `steps` calls between two syncs."""
+def time_steps(fn, steps: int, warmup: int, events: bool = False):
+    """Seconds per step: `warmup` untimed calls, then exactly `steps` calls between two syncs.
+    With `events`, also the seconds per step between two HIP events recorded on the launch
+    stream (torch's current stream, which the binding launches on) around the same calls."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    e0.record()
     for _ in range(steps):
         fn()
+    e1.record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    wall = (time.perf_counter() - t0) / steps
+    return (wall, e0.elapsed_time(e1) / 1e3 / steps) if events else wall
 
 
 def make_runner(wl: Workload, ws: hb.Workspace, use_graph: bool):
@@ -126,6 +137,33 @@ def kernel_profile(wl: Workload, ws: hb.Workspace, steps: int):
     finally:
         hb.hgf_profile_enable(False)
     return (dms, dn), (pms, pn)
+
+
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "decode_m1_config4_hbm_traffic.txt")
+
+
+def recorded_traffic():
+    """HBM bytes per decode launch from the committed counter summary (None if absent)."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(float(line.split("=")[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
+def copy_probe(mib: int) -> int:
+    """A plain copy of `mib` MiB (read once, written once) by an elementwise kernel, five times."""
+    n = mib * (1 << 20) // 4
+    src = torch.arange(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        torch.mul(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe_bytes_read": n * 4, "copy_probe_bytes_written": n * 4, "launches": 5}))
+    return 0
 
 
 def cpu_baseline(cfg: int, M: int, n_linears: int, budget_s: float):
@@ -169,6 +207,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--target-wgs", type=int, default=0, help="decode workgroups per launch (0 = library default)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="run only a plain copy kernel of this many MiB (counter calibration)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -181,6 +221,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        return copy_probe(args.copy_probe)
     if args.target_wgs:
         hb.hgf_set_decode_target_workgroups(args.target_wgs)
     use_graph = not args.no_graph
@@ -190,12 +232,19 @@ def main() -> int:
     # ---- primary: 7B-shape FFN decode, M = 1, distinct weights every block (HBM-cold)
     wl = Workload(4, 1, args.blocks, seed=4000, ws=ws)
     run = make_runner(wl, ws, use_graph)
-    sec = time_steps(run, args.steps, args.warmup)
+    sec, ev_sec = time_steps(run, args.steps, args.warmup, events=True)
     gbs = wl.bytes / sec / 1e9
-    (dms, dn), _ = kernel_profile(wl, ws, max(2, min(args.steps, 10)))    # a launch covers up+gate or down
-    avg_kernel_s = dms / 1e3 / max(dn, 1)
-    k_bytes = wl.main_bytes * max(2, min(args.steps, 10)) / max(dn, 1)   # algorithmic bytes per main-kernel launch
-    achieved = k_bytes / avg_kernel_s / 1e9 if dn else 0.0
+    # The decode kernel is the only kernel of a step: one launch per group of layers (up+gate,
+    # then down).  Its average launch duration over the timed region is the region's length
+    # between two HIP events on the launch stream divided by the launches in it (so the gaps
+    # between launches count against the kernel).  A second, eager pass brackets every launch
+    # with its own event pair; those pairs add a few microseconds each and are reported aside.
+    psteps = max(2, min(args.steps, 10))
+    (dms, dn), _ = kernel_profile(wl, ws, psteps)
+    launches_per_step = max(dn // psteps, 1)
+    avg_kernel_s = ev_sec / launches_per_step
+    k_bytes = wl.bytes / launches_per_step                               # algorithmic bytes per launch
+    achieved = k_bytes / avg_kernel_s / 1e9
 
     out = {
         "metric": "HGF linear achieved HBM GB/s at M=1 (7B-shape FFN decode)",
@@ -220,16 +269,17 @@ def main() -> int:
             "launch": "hip-graph replay" if use_graph else "eager",
         },
         "roofline": {
-            "kernel": "decode_kernel<1> (grouped main kernel: up+gate in one launch, down in the next)",
+            "kernel": "fused_kernel (one persistent launch per group of layers: up+gate, then down)",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": recorded_traffic(),
             "avg_launch_us": round(avg_kernel_s * 1e6, 3),
-            "launches_timed": int(dn),
+            "launches_timed": int(launches_per_step * args.steps),
             "algorithmic_bytes_per_launch": int(k_bytes),
+            "per_launch_event_pairs_us": round(dms * 1e3 / max(dn, 1), 3),
         },
     }
 
