@@ -62,11 +62,13 @@ size_t hgf_packed_weight_bytes(int d_out, int d_in);
  * d_out <= d_out_max, rank <= rank_max needs.  0 on invalid sizes. */
 size_t hgf_workspace_bytes(int M_max, int d_in_max, int d_out_max, int rank_max);
 
-/* Clears a workspace.  Must be called once (and again after any call that returned
- * HGF_ERR_DEVICE) before the workspace is used: the forward calls keep a region of
- * split-K accumulators and arrival counters that they expect to find zero and leave
- * zero.  A workspace serves one call at a time: calls that share one must be
- * ordered on a single stream. */
+/* Prepares a workspace.  Must be called once (and again after any call that returned
+ * HGF_ERR_DEVICE) before the workspace is used: the few-token path keeps a launch counter, an
+ * arrival count and a sticky error word at the start of the workspace (zeroed here) and two
+ * exchange buffers that hold a sentinel bit pattern between launches (filled here).  The
+ * error word (int32 at byte offset 8) becomes nonzero if a bounded in-kernel wait ever runs
+ * out; the outputs of that launch are then NaN.  A workspace serves one call at a time:
+ * calls that share one must be ordered on a single stream. */
 hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------- weights (offline)

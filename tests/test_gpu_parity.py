@@ -142,7 +142,7 @@ def test_zero_token_and_extreme_accumulators(ws):
 
 
 def test_repeated_calls_reuse_the_workspace(ws):
-    """Split-K scratch and counters are left clean: the same call twice, then a different
+    """The workspace carries nothing from one call into the next: the same call twice, then a different
     shape, all on one workspace, give the oracle's integers every time."""
     a = synth.make_custom(5, 1, 4096, 512, 64)
     b = synth.make_custom(6, 16, 2048, 1024, 32)
