@@ -10,9 +10,8 @@ Default workload: the 7B-shape FFN decode at M=1 (up, gate: 4096->11008; down:
 parameters per step, so every step streams its weights from HBM (nothing fits in cache).
 `value` is the achieved HBM GB/s over the algorithmic bytes of the step.  The same JSON
 line also carries: tokens/s, the roofline record of the decode kernel (one persistent
-launch per group of layers: up+gate, then down; its duration measured with HIP events on
-the launch stream in a second pass; its HBM traffic from the committed counter summary
-under profiles/), the CPU oracle timed on a bounded sample, and secondary cases (the
+launch per run of layers, two per step; its duration measured with HIP events on the
+launch stream; its HBM traffic from the committed counter summary under profiles/), the CPU oracle timed on a bounded sample, and secondary cases (the
 8-layer d=512 stack at M=1, the 1.2B-shape layer at M=1, the 3B-shape prefill layer at
 M=2048).
 
@@ -234,11 +233,12 @@ def main() -> int:
     run = make_runner(wl, ws, use_graph)
     sec, ev_sec = time_steps(run, args.steps, args.warmup, events=True)
     gbs = wl.bytes / sec / 1e9
-    # The decode kernel is the only kernel of a step: one launch per group of layers (up+gate,
-    # then down).  Its average launch duration over the timed region is the region's length
-    # between two HIP events on the launch stream divided by the launches in it (so the gaps
-    # between launches count against the kernel).  A second, eager pass brackets every launch
-    # with its own event pair; those pairs add a few microseconds each and are reported aside.
+    # The decode kernel is the only kernel of a step: one persistent launch per run of layers
+    # (as many as one launch's description holds: 16 FFN blocks, so two launches per step).
+    # Its average launch duration over the timed region is the region's length between two
+    # HIP events on the launch stream divided by the launches in it (gaps between launches
+    # count against the kernel).  A second, eager pass brackets every launch with its own
+    # event pair and is reported aside.
     psteps = max(2, min(args.steps, 10))
     (dms, dn), _ = kernel_profile(wl, ws, psteps)
     launches_per_step = max(dn // psteps, 1)
@@ -269,7 +269,7 @@ def main() -> int:
             "launch": "hip-graph replay" if use_graph else "eager",
         },
         "roofline": {
-            "kernel": "fused_kernel (one persistent launch per group of layers: up+gate, then down)",
+            "kernel": "stack_kernel (one persistent launch per run of 16 FFN blocks = 32 groups of layers)",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,

@@ -166,11 +166,13 @@ hgf_status hgf_profile_collect(double *ms_out, long long *launches_out);
  * launch aims at when it splits d_in across workgroups; 0 restores the default. */
 void hgf_set_decode_target_workgroups(int n);
 
-/* Tuning hook (host state, not thread-safe): calls with at most 4 tokens, d_in % 8 == 0 and
- * d_in <= 12288 normally run each group of layers as one persistent launch; 0 sends them
- * down the two-launch path that serves 5..64 tokens instead.  Results agree bit for bit in
- * the integers; the fp16 outputs may differ in the last place (different split of A x). */
-void hgf_set_single_launch(int on);
+/* Tuning hook (host state, not thread-safe) for calls with at most 4 tokens, d_in % 8 == 0 and
+ * d_in <= 12288.  level 2 (default): hgf_stack_forward runs whole runs of groups of layers as
+ * one persistent launch (activations handed from layer to layer inside the launch), and
+ * single groups as level 1; level 1: each group of layers is one persistent launch;
+ * level 0: the two-launch path that serves 5..64 tokens.  Results agree bit for bit in the
+ * integers; the fp16 outputs may differ in the last place (different split of A x). */
+void hgf_set_single_launch(int level);
 
 #ifdef __cplusplus
 }

@@ -131,8 +131,9 @@ def hgf_workspace_init(ws: Workspace, stream=None) -> None:
     _check(lib().hgf_workspace_init(ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_workspace_init")
 
 
-def hgf_set_single_launch(on: bool) -> None:
-    lib().hgf_set_single_launch(1 if on else 0)
+def hgf_set_single_launch(level) -> None:
+    """0: two launches per group; 1 (or True): one persistent launch per group; 2: per stack."""
+    lib().hgf_set_single_launch(int(level))
 
 
 def hgf_set_decode_target_workgroups(n: int) -> None:

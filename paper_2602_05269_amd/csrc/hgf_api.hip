@@ -19,6 +19,7 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     };
     ws.flags = reinterpret_cast<int32_t *>(take(kZeroBytes));
     ws.mail = reinterpret_cast<unsigned char *>(take(2 * kMailBytes));
+    ws.xchg = reinterpret_cast<unsigned char *>(take(2 * kStackSetBytes));
     const int Kp = round_up(d_in, kTileCols);
     ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
@@ -59,7 +60,7 @@ hgf_status from_hip(hipError_t e) { return e == hipSuccess ? HGF_OK : HGF_ERR_DE
 
 // Profiling aid: event pairs recorded around main-kernel launches, by kind (0 decode, 1 prefill).
 bool g_profile = false;
-bool g_single_launch = true;
+int g_launch_level = 2;      // 0: two launches per group, 1: one persistent launch per group, 2: per stack
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events[2];
 std::vector<hipEvent_t> g_event_pool;
 
@@ -102,7 +103,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
                             int32_t *acc_debug, const Workspace &ws, hipStream_t st)
 {
     const int K = layers[0].d_in;
-    bool fused = g_single_launch && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
+    bool fused = g_launch_level >= 1 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
     for (int g = 0; g < G; ++g)
         fused = fused && (layers[g].rank == 0 ||
                           (layers[g].rank % 8 == 0 && aligned16(layers[g].A_f16) && aligned16(layers[g].B_f16) &&
@@ -239,7 +240,8 @@ hgf_status hgf_workspace_init(void *workspace, size_t workspace_bytes, void *str
     if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (launch_fill(ws.flags, align256(kZeroBytes), 0u, st) != hipSuccess) return HGF_ERR_DEVICE;
-    return from_hip(launch_fill(ws.mail, 2 * kMailBytes, 0xFFFFFFFFu, st));
+    if (launch_fill(ws.mail, 2 * kMailBytes, 0xFFFFFFFFu, st) != hipSuccess) return HGF_ERR_DEVICE;
+    return from_hip(launch_fill(ws.xchg, 2 * kStackSetBytes, 0xFFFFFFFFu, st));
 }
 
 hgf_status hgf_quantize_pack_weights(const float *W, int d_out, int d_in, void *packed_out, float *s_w_out,
@@ -318,10 +320,12 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
     const Workspace ws = carve_workspace(workspace, M, d_in_max, d_out_max, rank_max);
     if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    int i = 0;
-    while (i < n_layers) {
-        // a group: consecutive layers reading the same slot with the same d_in, none of which
-        // writes that slot or a slot another member writes
+
+    // groups: consecutive layers reading the same slot with the same d_in, none of which writes
+    // that slot or a slot another member writes
+    struct Group { int first, G; bool stackable; };
+    std::vector<Group> groups;
+    for (int i = 0; i < n_layers;) {
         int G = 1;
         while (i + G < n_layers && G < kMaxGroup) {
             const hgf_layer &C = layers[i + G];
@@ -330,20 +334,106 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
             if (!ok) break;
             ++G;
         }
-        const void *x = slots[layers[i].src_slot];
+        const int K = layers[i].d_in;
+        bool stackable = g_launch_level >= 2 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK;
+        for (int g = 0; g < G && stackable; ++g) {
+            const hgf_layer &L = layers[i + g];
+            stackable = L.d_out % 8 == 0 &&
+                        (L.rank == 0 || (L.rank % 8 == 0 && aligned16(L.A_f16) && aligned16(L.B_f16) &&
+                                         (reinterpret_cast<uintptr_t>(L.alpha_f16) & 3u) == 0));
+        }
+        groups.push_back({i, G, stackable});
+        i += G;
+    }
+
+    auto run_group = [&](const Group &gr) -> hgf_status {
+        const void *x = slots[layers[gr.first].src_slot];
         if (M <= kMaxDecodeM) {
             void *ys[kMaxGroup];
-            for (int g = 0; g < G; ++g) ys[g] = slots[layers[i + g].dst_slot];
-            const hgf_status s = run_decode_group(x, M, layers + i, G, ys, nullptr, ws, st);
+            for (int g = 0; g < gr.G; ++g) ys[g] = slots[layers[gr.first + g].dst_slot];
+            return run_decode_group(x, M, layers + gr.first, gr.G, ys, nullptr, ws, st);
+        }
+        for (int g = 0; g < gr.G; ++g) {
+            const hgf_layer &L = layers[gr.first + g];
+            const hgf_status s = run_large_layer(x, M, L, slots[L.dst_slot], nullptr, ws, g == 0, st);
             if (s != HGF_OK) return s;
-        } else {
-            for (int g = 0; g < G; ++g) {
-                const hgf_status s = run_large_layer(x, M, layers[i + g], slots[layers[i + g].dst_slot], nullptr, ws,
-                                                     g == 0, st);
-                if (s != HGF_OK) return s;
+        }
+        return HGF_OK;
+    };
+
+    // Runs groups [a, b), all stackable, as one persistent launch; false if they do not fit it.
+    auto run_stack = [&](size_t a, size_t b) -> bool {
+        StackParams sp;
+        sp.M = M;
+        sp.nphases = (int)(b - a);
+        sp.flags = ws.flags;
+        sp.xchg = ws.xchg;
+        int nl = 0;
+        size_t act = 0;
+        for (size_t gi = a; gi < b; ++gi) {
+            const Group &gr = groups[gi];
+            StackPhase &P = sp.ph[gi - a];
+            P.K = layers[gr.first].d_in;
+            P.first_layer = (short)nl;
+            P.G = (short)gr.G;
+            // the tokens: the latest earlier layer of this launch that writes the slot, else the slot itself
+            const int src = layers[gr.first].src_slot;
+            P.x_ext = reinterpret_cast<const _Float16 *>(slots[src]);
+            P.src_off = 0;
+            for (int j = 0; j < nl; ++j) {
+                if (layers[groups[a].first + j].dst_slot == src) {
+                    P.x_ext = nullptr;
+                    P.src_off = sp.L[j].act_off;
+                }
+            }
+            for (int g = 0; g < gr.G; ++g) {
+                const hgf_layer &L = layers[gr.first + g];
+                StackLayer &D = sp.L[nl++];
+                D.packed = reinterpret_cast<const v4u *>(L.W_packed);
+                D.s_w = L.s_w;
+                D.A = reinterpret_cast<const _Float16 *>(L.A_f16);
+                D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
+                D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
+                D.y = reinterpret_cast<_Float16 *>(slots[L.dst_slot]);
+                D.N = L.d_out;
+                D.rank = L.rank;
+                D.act_off = (unsigned)act;
+                D.reserved = 0;
+                act += align256((size_t)M * L.d_out * 2);
             }
         }
-        i += G;
+        if (act > kStackActBytes) return false;
+        sp.act_used = (unsigned)act;
+        size_t lds_bytes = 0;
+        if (!plan_stack(sp, &lds_bytes)) return false;
+        ProfileScope prof(0, st);
+        return launch_stack(sp, lds_bytes, st) == hipSuccess;
+    };
+
+    size_t gi = 0;
+    while (gi < groups.size()) {
+        // the longest run of stackable groups that fits one launch's description
+        size_t ge = gi;
+        int nl = 0;
+        size_t act = 0;
+        while (ge < groups.size() && groups[ge].stackable && (int)(ge - gi) < kStackMaxPhases &&
+               nl + groups[ge].G <= kStackMaxLayers) {
+            size_t add = 0;
+            for (int g = 0; g < groups[ge].G; ++g) add += align256((size_t)M * layers[groups[ge].first + g].d_out * 2);
+            if (act + add > kStackActBytes) break;
+            act += add;
+            nl += groups[ge].G;
+            ++ge;
+        }
+        if (ge - gi >= 2 && run_stack(gi, ge)) {
+            gi = ge;
+            continue;
+        }
+        if (ge == gi) ge = gi + 1;
+        for (; gi < ge; ++gi) {
+            const hgf_status s = run_group(groups[gi]);
+            if (s != HGF_OK) return s;
+        }
     }
     return HGF_OK;
 }
@@ -375,6 +465,6 @@ hgf_status hgf_profile_collect(double *ms_out, long long *launches_out)
 /* Tuning hook for benchmarks: target number of decode workgroups per launch (0 = default). */
 void hgf_set_decode_target_workgroups(int n) { set_decode_target_wgs(n); }
 
-void hgf_set_single_launch(int on) { g_single_launch = on != 0; }
+void hgf_set_single_launch(int level) { g_launch_level = level < 0 ? 0 : (level > 2 ? 2 : level); }
 
 }  // extern "C"

@@ -124,6 +124,7 @@ struct Workspace {
     int32_t *flags;      // zero region: [0] correction workgroups done, [1] decode workgroups done,
                          // [2] sticky: a bounded wait ran out
     unsigned char *mail; // two exchange buffers of kMailBytes, sentinel-filled between launches
+    unsigned char *xchg; // two sets of kStackSetBytes for the whole-stack launch, likewise
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
@@ -137,13 +138,13 @@ struct Workspace {
 // Carves `base` for a call of the given sizes (base may be null: sizes only).
 Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank);
 
-inline int h_rank_tiles(int rank)   // rank tiles of 16, rounded to a power of two (1, 2, 4, 8)
+__host__ __device__ inline int h_rank_tiles(int rank)   // rank tiles of 16, rounded to a power of two (1, 2, 4, 8)
 {
     int t = (rank + 15) / 16, p = 1;
     while (p < t) p *= 2;
     return p;
 }
-inline int h_stride(int rank)       // row stride of h16 in elements (multiple of 32)
+__host__ __device__ inline int h_stride(int rank)       // row stride of h16 in elements (multiple of 32)
 {
     int s = 16 * h_rank_tiles(rank);
     return s < 32 ? 32 : s;
@@ -159,6 +160,7 @@ struct ProLayer {
 struct ProParams {
     const _Float16 *x;
     unsigned char *mail; // two exchange buffers of kMailBytes, sentinel-filled between launches
+    unsigned char *xchg; // two sets of kStackSetBytes for the whole-stack launch, likewise
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
@@ -214,6 +216,39 @@ struct FusedParams {
     int32_t *flags;               // [0] launch counter, [1] workgroups done, [2] sticky: a wait ran out
 };
 
+// One persistent launch over a list of phases (groups of layers) for a handful of tokens.
+// Sized so that the whole description fits the 4 KiB of kernel arguments.
+constexpr int kStackMaxLayers = 48;
+constexpr int kStackMaxPhases = 36;
+constexpr size_t kStackActBytes = size_t(6) << 20;     // per set: exchange copies of the layers' outputs ...
+constexpr size_t kStackSetBytes = size_t(8) << 20;     // ... followed by the partial sums of A x
+struct StackLayer {                                    // 64 bytes
+    const v4u *packed;
+    const float *s_w;
+    const _Float16 *A, *B, *alpha;
+    _Float16 *y;
+    int N, rank;
+    unsigned act_off;             // byte offset of the output's exchange copy ([M][N] fp16, N % 8 == 0)
+    int reserved;
+};
+struct StackPhase {                                    // 24 bytes
+    const _Float16 *x_ext;        // the tokens, when they were written before the launch; else null
+    int K;
+    short first_layer, G;
+    unsigned src_off;             // else: byte offset of their exchange copy
+    unsigned mail_off;            // byte offset of the phase's partial sums of A x
+};
+struct StackParams {
+    int M, nphases, nwg, reserved;
+    int32_t *flags;               // [2] sticky error, [4] launch counter, [5] workgroups done, [6], [7] extents used
+    unsigned char *xchg;          // two sets of kStackSetBytes
+    unsigned act_used, mail_used;
+    int xstride, xh_off, tile_off, h_off, unit_off, unit_stride, unit_alpha, reserved2;   // LDS layout
+    StackPhase ph[kStackMaxPhases];
+    StackLayer L[kStackMaxLayers];
+};
+static_assert(sizeof(StackParams) <= 4096, "kernel arguments");
+
 // ---- kernel launchers (each validates nothing: the ABI layer has done it) -----------
 hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_out, hipStream_t st);
 hipError_t launch_pack(const float *W, int N, int K, const float *s_w, uint32_t *packed, hipStream_t st);
@@ -229,6 +264,8 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
 bool plan_fused(FusedParams &p, size_t *lds_bytes);
 hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);
 int decode_target_waves();
+bool plan_stack(StackParams &p, size_t *lds_bytes);
+hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
 void set_decode_target_wgs(int v);
 hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
                           hipStream_t st);

@@ -1,0 +1,734 @@
+// A whole list of layers for a handful of tokens (M <= 4) in ONE persistent launch.
+//
+// Algorithm 1 of the HGF paper, steps 1-8, for every layer of a stack.  Launching each group
+// of layers on its own leaves two thirds of the time in launch gaps and start-up latency
+// (first touch of the activations, cold translation, kernel arguments).  Here the workgroups
+// (one per compute unit) stay resident for the whole list and walk it phase by phase -- a
+// phase is a group of up to four layers that read the same activations:
+//
+//   * seven streaming wavefronts keep a ring of weight tiles in flight across phase
+//     boundaries: weights do not depend on activations, so while a phase waits for its input
+//     the memory system keeps delivering its first tiles;
+//   * one service wavefront fetches the phase's input, computes its slice of A x, collects
+//     all slices, and finishes the units its workgroup owns (dequantise, B h, gate, store).
+//
+// Activations pass from one phase to the next through the workspace: the service wavefronts
+// store every output both to the caller's slot and, with device scope, to an exchange
+// region that holds a sentinel bit pattern (all ones) wherever nothing has been written;
+// readers re-read with device scope until no word is the sentinel.  No flag, no fence, no
+// grid barrier.  (An output that is NaN is stored as the canonical quiet NaN, which is not
+// the sentinel.)  The partial sums of A x travel the same way.  Two sets of regions
+// alternate from launch to launch by a counter in the workspace; each launch refills, in the
+// other set, what the previous launch used.  Every wait is bounded; on expiry a sticky word
+// is set in the workspace, the affected outputs are NaN and later waits are skipped.
+//
+// Inside a workgroup the two sides meet at three barriers per phase (input in LDS; absmax;
+// quantised input in LDS) and through LDS counters per unit.
+#include "hgf_internal.h"
+
+namespace hgf {
+
+namespace {
+
+constexpr int kStream = 7;             // streaming wavefronts per workgroup (wavefront 7 is the service one)
+#ifndef HGF_STACK_PF
+#define HGF_STACK_PF 8
+#endif
+constexpr int kPF = HGF_STACK_PF;      // weight tiles in flight per streaming wavefront
+constexpr int kMaxUnits = 16;          // units per workgroup and phase at most
+constexpr int kLdsPolls = 1 << 22;     // bound of a wait on LDS (about a second)
+constexpr int kMemPolls = 1 << 18;     // bound of a wait on an exchange region (about a second)
+constexpr unsigned kSentinel = 0xFFFFFFFFu;
+constexpr int kHsStride = HGF_MAX_RANK;  // halves per (layer, token) row of SiLU(A x) in LDS
+constexpr int kUN = 8;                 // 64-column steps of a slice of A x requested together
+constexpr int kSplit = kFusedSplit;    // slices of d_in at most
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+
+struct Control {                       // LDS words shared by the two sides, one set per phase parity
+    int arrived[2][kMaxUnits];         // streaming wavefronts that have posted the unit
+    int rowsum[2][kMaxFusedM];
+    float amax_part[kStream][kMaxFusedM];
+    float sx[2][kMaxFusedM];
+};
+
+__device__ __forceinline__ int lds_load(const int *p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
+__device__ __forceinline__ v4u load16_agent(rsrc_t r, unsigned off, bool ok = true)
+{
+    return __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(r, (int)(ok ? off : kOob), 0, 16));
+}
+__device__ __forceinline__ void store16_agent(rsrc_t r, unsigned off, v4u v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 16);
+}
+__device__ __forceinline__ bool has_sentinel(v4u v)
+{
+    return v[0] == kSentinel || v[1] == kSentinel || v[2] == kSentinel || v[3] == kSentinel;
+}
+__device__ __forceinline__ float exp_fast(float v) { return __builtin_amdgcn_exp2f(v * 1.44269504088896340736f); }
+__device__ __forceinline__ float silu_fast(float h) { return h * __builtin_amdgcn_rcpf(1.0f + exp_fast(-h)); }
+__device__ __forceinline__ float tanh_fast(float a) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_fast(2.0f * a)); }
+__device__ __forceinline__ void bare_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// What both sides derive from a phase's entry in the kernel arguments (all wave-uniform).
+struct PhaseShape {
+    int K, Kp, KT, TPW, G, first;      // first: index of the phase's first layer
+    int units, nunits;                 // row-blocks of the phase; of this workgroup
+    int us1, us2, us3;                 // running sums of the layers' row-blocks (0x7fffffff beyond G)
+};
+__device__ __forceinline__ PhaseShape shape_of(const StackParams &p, int ph, int c)
+{
+    PhaseShape s;
+    const StackPhase &P = p.ph[ph];
+    s.K = P.K;
+    s.Kp = (s.K + kTileCols - 1) / kTileCols * kTileCols;
+    s.KT = s.Kp / kTileCols;
+    s.TPW = (s.KT + kStream - 1) / kStream;
+    s.G = P.G;
+    s.first = P.first_layer;
+    const int r0 = (p.L[s.first].N + kTileRows - 1) / kTileRows;
+    const int r1 = s.G > 1 ? (p.L[s.first + 1].N + kTileRows - 1) / kTileRows : 0;
+    const int r2 = s.G > 2 ? (p.L[s.first + 2].N + kTileRows - 1) / kTileRows : 0;
+    const int r3 = s.G > 3 ? (p.L[s.first + 3].N + kTileRows - 1) / kTileRows : 0;
+    s.us1 = s.G > 1 ? r0 : 0x7fffffff;
+    s.us2 = s.G > 2 ? r0 + r1 : 0x7fffffff;
+    s.us3 = s.G > 3 ? r0 + r1 + r2 : 0x7fffffff;
+    s.units = r0 + r1 + r2 + r3;
+    s.nunits = c < s.units ? (s.units - c + p.nwg - 1) / p.nwg : 0;
+    return s;
+}
+// steps of a streaming wavefront's ring in a phase: its tiles, padded to whole turns of the ring
+// (at least one turn, so that the cursor never has to loop over empty phases)
+__device__ __forceinline__ int ring_steps(const PhaseShape &s)
+{
+    const int n = (s.nunits * s.TPW + kPF - 1) / kPF * kPF;
+    return n > 0 ? n : kPF;
+}
+
+// ------------------------------------------------------------------ streaming side
+__device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
+{
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int jl = l & 31, hf = l >> 5;
+    constexpr int nthreads = kStream * 64;
+
+    // ---- load cursor: phase lp, step ls of its padded ring sequence (unit li, tile lj)
+    int lp = 0, ls = 0, li = 0, lj = 0, lsteps = 0;
+    PhaseShape LS;
+    const void *pk0 = nullptr, *pk1 = nullptr, *pk2 = nullptr, *pk3 = nullptr;
+    unsigned by0 = 0, by1 = 0, by2 = 0, by3 = 0;
+    const void *lbase = nullptr;
+    unsigned lbytes = 0, lrow = 0;
+    auto load_unit = [&]() {            // the load cursor has entered unit li of phase lp
+        const bool valid = lp < p.nphases && li < LS.nunits;
+        const int u = valid ? c + li * p.nwg : 0;
+        int first = 0;
+        lbase = pk0;
+        lbytes = by0;
+        if (u >= LS.us1) { lbase = pk1; lbytes = by1; first = LS.us1; }
+        if (u >= LS.us2) { lbase = pk2; lbytes = by2; first = LS.us2; }
+        if (u >= LS.us3) { lbase = pk3; lbytes = by3; first = LS.us3; }
+        if (!valid) lbytes = 0;         // padding steps and steps past the last phase read zeros
+        lrow = (unsigned)(u - first) * LS.KT;
+    };
+    auto load_phase = [&]() {           // the load cursor has entered phase lp
+        if (lp < p.nphases) {
+            LS = shape_of(p, lp, c);
+            const StackLayer *L = p.L + LS.first;
+            pk0 = L[0].packed;
+            by0 = (unsigned)((L[0].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes;
+            pk1 = LS.G > 1 ? L[1].packed : nullptr;
+            by1 = LS.G > 1 ? (unsigned)((L[1].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes : 0u;
+            pk2 = LS.G > 2 ? L[2].packed : nullptr;
+            by2 = LS.G > 2 ? (unsigned)((L[2].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes : 0u;
+            pk3 = LS.G > 3 ? L[3].packed : nullptr;
+            by3 = LS.G > 3 ? (unsigned)((L[3].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes : 0u;
+            lsteps = ring_steps(LS);
+        } else {
+            lsteps = 0x7fffffff;        // past the end: zeros for ever
+        }
+        ls = 0;
+        li = 0;
+        lj = 0;
+        load_unit();
+    };
+    load_phase();
+    v4u wq[kPF];
+    auto issue = [&](v4u &dst) {
+        const int kt = lj * kStream + w;
+        const rsrc_t wr = make_rsrc(lbase, lbytes);
+        dst = buf_load16_stream(wr, kt < LS.KT ? (lrow + kt) * kTileBytes + l * 16 : kOob);
+        ++ls;
+        if (++lj == LS.TPW) {
+            lj = 0;
+            ++li;
+            load_unit();
+        }
+        if (ls == lsteps) {
+            ++lp;
+            load_phase();
+        }
+    };
+#pragma unroll
+    for (int t = 0; t < kPF; ++t) issue(wq[t]);
+
+    const _Float16 *xh = reinterpret_cast<const _Float16 *>(lds + p.xh_off);
+    for (int ph = 0; ph < p.nphases; ++ph) {
+        const PhaseShape S = shape_of(p, ph, c);
+        const int par = ph & 1;
+        bare_barrier();                 // A: the service wavefront has put the phase's tokens (fp16) into LDS
+        // ---- per-token absmax int8 quantisation into LDS (Sec. 2.2.1)
+        if (S.nunits > 0) {
+            for (int m = 0; m < p.M; ++m) {
+                float amax = 0.0f;
+                for (int i = tid; i < S.K / 8; i += nthreads) {
+                    const v8h a = __builtin_elementwise_abs(*reinterpret_cast<const v8h *>(xh + (size_t)m * S.K + i * 8));
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, (float)a[e]);
+                }
+                amax = wave_max(amax);
+                if (l == 0) ctl->amax_part[w][m] = amax;
+            }
+        }
+        __syncthreads();                // B: every wavefront's part of the absmax
+        if (S.nunits > 0) {
+            for (int m = 0; m < p.M; ++m) {
+                float amax = ctl->amax_part[0][m];
+#pragma unroll
+                for (int i = 1; i < kStream; ++i) amax = fmaxf(amax, ctl->amax_part[i][m]);
+                amax = fmaxf(amax, 1e-5f);
+                const float inv = 127.0f / amax;
+                int sum = 0;
+                for (int i = tid; i < S.Kp / 8; i += nthreads) {
+                    v8h v = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (i < S.K / 8) v = *reinterpret_cast<const v8h *>(xh + (size_t)m * S.K + i * 8);
+                    uint32_t q2[2] = {0u, 0u};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int q = quant1((float)v[e], inv);
+                        sum += q;
+                        q2[e >> 2] |= (uint32_t)(q & 0xff) << (8 * (e & 3));
+                    }
+                    *reinterpret_cast<uint2 *>(lds + m * p.xstride + i * 8) = make_uint2(q2[0], q2[1]);
+                }
+                sum = wave_sum(sum);
+                if (l == 0) {
+                    __hip_atomic_fetch_add(&ctl->rowsum[par][m], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (w == 0) ctl->sx[par][m] = amax / 127.0f;
+                }
+            }
+        }
+        __syncthreads();                // C: the quantised tokens are in LDS
+
+        // ---- contraction: one ring slot per step.  Straight-line code: the refill of a slot is
+        //      unconditional and the loop has no inner loop (either would cost the ring its
+        //      precise wait counts), and so are the MFMAs: a slot past the row-block's last
+        //      tile holds zeros, which add nothing.  The tokens are the matrix rows, so lanes
+        //      without a token simply read token 0: their rows of the result are never used.
+        //      The token operands of the next step are read from LDS while this step computes.
+        int *tiles = reinterpret_cast<int *>(lds + p.tile_off) + par * kMaxUnits * kMaxFusedM * kTileRows;
+        const int steps = ring_steps(S);
+        const unsigned char *xlane = lds + (jl < p.M ? jl : 0) * p.xstride + hf * 16;
+        auto xload = [&](v4i (&dst)[4], int j) {
+            int kt = j * kStream + w;
+            kt = kt < S.KT ? kt : S.KT - 1;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dst[q] = *reinterpret_cast<const v4i *>(xlane + kt * kTileCols + q * 32);
+        };
+        int ci = 0, cj = 0;
+        v16i acc = (v16i){};
+        v4i xv[2][4];
+        xload(xv[0], 0);
+        for (int s0 = 0; s0 < steps; s0 += kPF) {
+#pragma unroll
+            for (int t = 0; t < kPF; ++t) {
+                const int nj = cj + 1 == S.TPW ? 0 : cj + 1;
+                xload(xv[(t + 1) & 1], nj);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(xv[t & 1][q], widen_codes(wq[t][q]), acc, 0, 0, 0);
+                issue(wq[t]);
+                cj = nj;
+                if (nj == 0) {
+                    if (ci < S.nunits) {
+                        if (l < 32) {
+#pragma unroll
+                            for (int m = 0; m < kMaxFusedM; ++m)
+                                if (m < p.M)
+                                    __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + l, acc[m],
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        }
+                        if (l == 0)
+                            __hip_atomic_fetch_add(&ctl->arrived[par][ci], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+                    acc = (v16i){};
+                    ++ci;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ service side
+struct JobRegs {
+    v8h a[kUN][2];
+};
+// Requests the rows of A for one batch of a slice: lane (i = l%16, kb = l/16) holds
+// A[rt*16+i][k] for k = 64*kp + 16*kb + 0..7 and + 8..15.
+__device__ __forceinline__ void job_load(JobRegs &r, const _Float16 *A, int rank, int K, int rt, int kpb, int kp1)
+{
+    const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
+    const int j = rt * 16 + i;
+    const rsrc_t ar = make_rsrc(A, (unsigned)rank * K * 2u);
+#pragma unroll
+    for (int u = 0; u < kUN; ++u) {
+        const int k0 = (kpb + u) * 64 + kb * 16;
+        const bool ok = (kpb + u) < kp1 && j < rank;
+        r.a[u][0] = buf_load8h<true>(ar, (unsigned)j * K + k0, K - k0, ok);
+        r.a[u][1] = buf_load8h<true>(ar, (unsigned)j * K + k0 + 8, K - k0 - 8, ok);
+    }
+}
+// The tokens' side comes from the fp16 copy in LDS.
+__device__ __forceinline__ v4f job_mfma(const JobRegs &r, const _Float16 *xh, int M, int K, int kpb, int kp1, v4f acc)
+{
+    const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
+#pragma unroll
+    for (int u = 0; u < kUN; ++u) {
+        const int k0 = (kpb + u) * 64 + kb * 16;
+        v8h b0 = {0, 0, 0, 0, 0, 0, 0, 0}, b1 = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (i < M && (kpb + u) < kp1) {
+            if (k0 < K) b0 = *reinterpret_cast<const v8h *>(xh + (size_t)i * K + k0);
+            if (k0 + 8 < K) b1 = *reinterpret_cast<const v8h *>(xh + (size_t)i * K + k0 + 8);
+        }
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][0], b0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][1], b1, acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+// Requests the epilogue operands of a unit into LDS (see hgf_fused.hip: B rows as 16-byte
+// pieces in column-major order, then the 32 gate parameters).
+__device__ __forceinline__ void stage_unit(const StackParams &p, const StackLayer &L, int n0, unsigned char *dst)
+{
+    const int l = threadIdx.x & 63, r = l & 31;
+    if (L.rank == 0) return;
+    const int hstride = h_stride(L.rank);
+    const rsrc_t br = make_rsrc(L.B, (unsigned)L.N * L.rank * 2u);
+    const rsrc_t ar = make_rsrc(L.alpha, ((unsigned)L.N * 2u + 3u) & ~3u);
+    const int ninstr = hstride / 16;
+    for (int k = 0; k < ninstr; ++k) {
+        const int cp = 2 * k + (l >> 5);
+        const bool ok = cp * 8 < L.rank && n0 + r < L.N;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(br, (lds_ptr_t)(dst + k * 1024), 16,
+                                                 (int)(ok ? (unsigned)((n0 + r) * L.rank + cp * 8) * 2u : kOob), 0, 0, 0);
+    }
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(ar, (lds_ptr_t)(dst + p.unit_alpha), 4,
+                                             (int)(l < 16 && n0 + 2 * l < L.N ? (unsigned)(n0 * 2 + l * 4) : kOob), 0, 0, 0);
+}
+
+template <int JS>
+__device__ __forceinline__ v16f corr_unit(const _Float16 *hrow, const unsigned char *brow, bool token)
+{
+    v8h hv[JS], bv[JS];
+#pragma unroll
+    for (int js = 0; js < JS; ++js) {
+        hv[js] = (v8h){0, 0, 0, 0, 0, 0, 0, 0};
+        if (token) hv[js] = *reinterpret_cast<const v8h *>(hrow + js * 16);
+        bv[js] = *reinterpret_cast<const v8h *>(brow + js * 1024);
+    }
+    v16f c0 = (v16f){}, c1 = (v16f){};
+#pragma unroll
+    for (int js = 0; js < JS; js += 2) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(hv[js], bv[js], c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(hv[js + 1], bv[js + 1], c1, 0, 0, 0);
+    }
+    return c0 + c1;
+}
+
+// unit of a phase -> (layer within the phase, first row)
+__device__ __forceinline__ void unit_decode(const PhaseShape &S, int u, int &g, int &n0)
+{
+    g = 0;
+    int first = 0;
+    if (u >= S.us1) { g = 1; first = S.us1; }
+    if (u >= S.us2) { g = 2; first = S.us2; }
+    if (u >= S.us3) { g = 3; first = S.us3; }
+    n0 = (u - first) * kTileRows;
+}
+
+__device__ __forceinline__ void service_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
+{
+    const int l = threadIdx.x & 63, jl = l & 31, hf = l >> 5;
+    bool failed = false;
+
+    // ---- which set of exchange regions this launch uses; what the previous launch used in the other
+    const unsigned epoch = (unsigned)__hip_atomic_load(p.flags + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned prev_act = (unsigned)__hip_atomic_load(p.flags + 6, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned prev_mail = (unsigned)__hip_atomic_load(p.flags + 7, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
+    unsigned char *other = p.xchg + (size_t)((epoch & 1u) ^ 1u) * kStackSetBytes;
+    const rsrc_t act = make_rsrc(mine, (unsigned)kStackActBytes);
+    const rsrc_t mail = make_rsrc(mine + kStackActBytes, (unsigned)(kStackSetBytes - kStackActBytes));
+
+    _Float16 *xh = reinterpret_cast<_Float16 *>(lds + p.xh_off);
+    _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off);
+    unsigned char *ustage = lds + p.unit_off;
+    int *tiles_all = reinterpret_cast<int *>(lds + p.tile_off);
+
+    for (int ph = 0; ph < p.nphases; ++ph) {
+        const PhaseShape S = shape_of(p, ph, c);
+        const StackPhase &P = p.ph[ph];
+        const StackLayer *L = p.L + S.first;
+        const int par = ph & 1;
+        int *tiles = tiles_all + par * kMaxUnits * kMaxFusedM * kTileRows;
+
+        // ---- zero what the streaming side adds into during this phase
+        if (l < kMaxUnits) ctl->arrived[par][l] = 0;
+        if (l < kMaxFusedM) ctl->rowsum[par][l] = 0;
+        for (int e = l; e < S.nunits * kMaxFusedM * kTileRows; e += 64) tiles[e] = 0;
+
+        // ---- requests that do not depend on the tokens: epilogue operands of my units
+        //      (LDS-direct), weight scales, the rows of A for my slice
+        for (int i = 0; i < S.nunits; ++i) {
+            int g2, n0;
+            unit_decode(S, c + i * p.nwg, g2, n0);
+            stage_unit(p, L[g2], n0, ustage + i * p.unit_stride);
+        }
+        const unsigned swb0 = buf_load4(make_rsrc(L[0].s_w, 4u), 0u);
+        const unsigned swb1 = buf_load4(make_rsrc(S.G > 1 ? L[1].s_w : nullptr, S.G > 1 ? 4u : 0u), 0u);
+        const unsigned swb2 = buf_load4(make_rsrc(S.G > 2 ? L[2].s_w : nullptr, S.G > 2 ? 4u : 0u), 0u);
+        const unsigned swb3 = buf_load4(make_rsrc(S.G > 3 ? L[3].s_w : nullptr, S.G > 3 ? 4u : 0u), 0u);
+
+        // slices of A x of the phase: 512 columns each, at most kSplit and 64 (slice, token) rows
+        const int pairs = (S.K + 63) / 64;
+        int nsl = (pairs + 7) / 8;
+        if (nsl > kSplit) nsl = kSplit;
+        if (nsl > 64 / p.M) nsl = 64 / p.M;
+        const int pps = (pairs + nsl - 1) / nsl;
+        const int Sn = (pairs + pps - 1) / pps;
+        const int rk0 = L[0].rank, rk1 = S.G > 1 ? L[1].rank : 0, rk2 = S.G > 2 ? L[2].rank : 0,
+                  rk3 = S.G > 3 ? L[3].rank : 0;
+        const int hs0 = h_stride(rk0), hs1 = h_stride(rk1), hs2 = h_stride(rk2), hs3 = h_stride(rk3);
+        const int jb1 = (rk0 + 15) / 16 * Sn, jb2 = jb1 + (rk1 + 15) / 16 * Sn, jb3 = jb2 + (rk2 + 15) / 16 * Sn,
+                  njobs = jb3 + (rk3 + 15) / 16 * Sn;
+        // byte offsets of the layers' partial sums inside the phase's region: [slice][token][hstride] fp32
+        const unsigned mo0 = P.mail_off, mo1 = mo0 + (unsigned)(rk0 > 0 ? Sn * p.M * hs0 * 4 : 0),
+                       mo2 = mo1 + (unsigned)(rk1 > 0 ? Sn * p.M * hs1 * 4 : 0),
+                       mo3 = mo2 + (unsigned)(rk2 > 0 ? Sn * p.M * hs2 * 4 : 0);
+        int job = p.nwg - 1 - c;        // the highest workgroups, which own the fewest units, come first
+        JobRegs jr;
+        int g = 0, rt = 0, sp = 0, kp0 = 0, kp1 = 0, jrank = 0, jhs = 0;
+        unsigned jmo = 0;
+        const _Float16 *jA = nullptr;
+        auto job_decode = [&]() {
+            g = 0;
+            int first = 0;
+            jrank = rk0; jhs = hs0; jmo = mo0;
+            if (job >= jb1) { g = 1; first = jb1; jrank = rk1; jhs = hs1; jmo = mo1; }
+            if (job >= jb2) { g = 2; first = jb2; jrank = rk2; jhs = hs2; jmo = mo2; }
+            if (job >= jb3) { g = 3; first = jb3; jrank = rk3; jhs = hs3; jmo = mo3; }
+            jA = L[g].A;
+            rt = (job - first) / Sn;
+            sp = (job - first) % Sn;
+            kp0 = sp * pps;
+            kp1 = min(kp0 + pps, pairs);
+        };
+        if (job < njobs) {
+            job_decode();
+            job_load(jr, jA, jrank, S.K, rt, kp0, kp1);
+        }
+
+        // ---- the phase's tokens: from the caller's slot, or from the exchange region once
+        //      every word of it has been written; into LDS as fp16
+        {
+            const bool ext = P.x_ext != nullptr;
+            const rsrc_t xr = make_rsrc(P.x_ext, ext ? (unsigned)p.M * S.K * 2u : 0u);
+            const int pieces = p.M * S.K / 8;           // 16 bytes each
+            constexpr int kXB = 16;                     // one batch covers 8192 columns of a token
+            for (int i0 = 0; i0 < pieces; i0 += 64 * kXB) {
+                v4u v[kXB];
+                int polls = 0;
+                if (ext) {                  // (one kind of load per path: both at once would double the registers)
+#pragma unroll
+                    for (int u = 0; u < kXB; ++u) {
+                        const int i = i0 + u * 64 + l;
+                        v[u] = buf_load16(xr, (unsigned)i * 16u, i < pieces);
+                    }
+                } else {
+                    while (true) {
+                        bool ready = true;
+#pragma unroll
+                        for (int u = 0; u < kXB; ++u) {
+                            const int i = i0 + u * 64 + l;
+                            v[u] = load16_agent(act, P.src_off + (unsigned)i * 16u, i < pieces);
+                            ready = ready && !has_sentinel(v[u]);
+                        }
+                        if (failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
+                        if (++polls >= kMemPolls) {
+                            failed = true;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kXB; ++u) {
+                    const int i = i0 + u * 64 + l;
+                    if (i < pieces) *reinterpret_cast<v4u *>(xh + (size_t)i * 8) = v[u];
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only: the LDS writes above have landed
+        bare_barrier();                 // A: tokens in LDS (and the zeroed counters)
+        bare_barrier();                 // B
+        // ---- my slices of A x (step 5) while the others quantise
+        while (job < njobs) {
+            v4f acc = {0.f, 0.f, 0.f, 0.f};
+            acc = job_mfma(jr, xh, p.M, S.K, kp0, kp1, acc);
+            for (int kpb = kp0 + kUN; kpb < kp1; kpb += kUN) {
+                job_load(jr, jA, jrank, S.K, rt, kpb, kp1);
+                acc = job_mfma(jr, xh, p.M, S.K, kpb, kp1, acc);
+            }
+            // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of the layer
+            const int i = l & 15, kb = l >> 4;
+            store16_agent(mail, i < p.M ? jmo + (unsigned)(((sp * p.M + i) * jhs + rt * 16 + 4 * kb) * 4) : kOob,
+                          __builtin_bit_cast(v4u, acc));
+            job += p.nwg;
+            if (job < njobs) {
+                job_decode();
+                job_load(jr, jA, jrank, S.K, rt, kp0, kp1);
+            }
+        }
+        bare_barrier();                 // C
+
+        if (S.nunits > 0) {
+            // ---- collect every slice: h[g][m][j] = SiLU(sum_sp partial) (step 6); a lane takes four
+            //      consecutive ranks of one (layer, token); one batch of loads usually covers all
+            const int ge0 = rk0 > 0 ? p.M * hs0 / 4 : 0;
+            const int ge1 = ge0 + (rk1 > 0 ? p.M * hs1 / 4 : 0);
+            const int ge2 = ge1 + (rk2 > 0 ? p.M * hs2 / 4 : 0);
+            const int ge3 = ge2 + (rk3 > 0 ? p.M * hs3 / 4 : 0);
+            for (int f0 = 0; f0 < ge3; f0 += 64) {
+                const int f = f0 + l;
+                // per-lane layer: arithmetic on the comparison results (a chain of selects between
+                // these scalars gets turned into a table in private memory)
+                const int b0 = f >= ge0, b1 = f >= ge1, b2 = f >= ge2;
+                const int gg = b0 + b1 + b2;
+                const int first = b0 * ge0 + b1 * (ge1 - ge0) + b2 * (ge2 - ge1);
+                const int rank = rk0 + b0 * (rk1 - rk0) + b1 * (rk2 - rk1) + b2 * (rk3 - rk2);
+                const int hstride = hs0 + b0 * (hs1 - hs0) + b1 * (hs2 - hs1) + b2 * (hs3 - hs2);
+                const unsigned mo = mo0 + (unsigned)b0 * (mo1 - mo0) + (unsigned)b1 * (mo2 - mo1) + (unsigned)b2 * (mo3 - mo2);
+                const bool inside = f < ge3;
+                const int idx = f - first;
+                const int j = (idx * 4) % hstride;
+                const bool wanted = inside && j < (rank + 15) / 16 * 16;
+                const unsigned at = mo + (unsigned)idx * 16u;
+                const unsigned step = (unsigned)p.M * hstride * 4u;
+                v4f part[kSplit];
+                int polls = 0;
+                while (true) {
+                    bool ready = true;
+#pragma unroll
+                    for (int sl = 0; sl < kSplit; ++sl) {
+                        const v4u raw = load16_agent(mail, at + (unsigned)sl * step, wanted && sl < Sn);
+                        ready = ready && !has_sentinel(raw);
+                        part[sl] = __builtin_bit_cast(v4f, raw);
+                    }
+                    if (failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
+                    if (++polls >= kMemPolls) {
+                        failed = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                v4f h = part[0];
+#pragma unroll
+                for (int sl = 1; sl < kSplit; ++sl) h += part[sl];          // slice order: deterministic
+                if (inside) {
+                    v4h o;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[v] = (j + v < rank) ? (_Float16)silu_fast(h[v]) : (_Float16)0.0f;
+                    *reinterpret_cast<v4h *>(hs + (gg * p.M + idx * 4 / hstride) * kHsStride + j) = o;
+                }
+            }
+
+            // ---- per unit: lane n < 32 owns output row n of the unit for every token
+            for (int i = 0; i < S.nunits; ++i) {
+                const unsigned char *op = ustage + i * p.unit_stride;
+                int gg, n0;
+                unit_decode(S, c + i * p.nwg, gg, n0);
+                const StackLayer &Lg = L[gg];
+                const unsigned swb = gg == 0 ? swb0 : (gg == 1 ? swb1 : (gg == 2 ? swb2 : swb3));
+                const int hstride = gg == 0 ? hs0 : (gg == 1 ? hs1 : (gg == 2 ? hs2 : hs3));
+                int polls = 0;
+                while (!failed && lds_load(&ctl->arrived[par][i]) < kStream) {
+                    if (++polls >= kLdsPolls) {
+                        failed = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                v16f corr = (v16f){};
+                float gate = 0.f;
+                if (Lg.rank > 0) {
+                    gate = tanh_fast((float)*reinterpret_cast<const _Float16 *>(op + p.unit_alpha + jl * 2));
+                    const _Float16 *hrow = hs + (gg * p.M + jl) * kHsStride + hf * 8;
+                    const unsigned char *brow = op + (hf * 32 + jl) * 16;
+                    switch (hstride / 16) {
+                        case 2: corr = corr_unit<2>(hrow, brow, jl < p.M); break;
+                        case 4: corr = corr_unit<4>(hrow, brow, jl < p.M); break;
+                        default: corr = corr_unit<8>(hrow, brow, jl < p.M); break;
+                    }
+                }
+                const int n = n0 + l;
+                const float s_w = __builtin_bit_cast(float, swb);
+                const int Npad = (Lg.N + 7) & ~7;         // row pitch of the exchange copy (16-byte rows)
+#pragma unroll
+                for (int m = 0; m < kMaxFusedM; ++m) {
+                    if (m < p.M) {
+                        const int a = tiles[(i * kMaxFusedM + m) * kTileRows + jl] - ctl->rowsum[par][m];
+                        _Float16 o = (_Float16)((float)a * (ctl->sx[par][m] * s_w) + gate * corr[m]);
+                        if (o != o || failed) o = __builtin_bit_cast(_Float16, (unsigned short)0x7e00);
+                        if (l < 32 && n < Lg.N) Lg.y[(size_t)m * Lg.N + n] = o;
+                        // exchange copy: 32 lanes x 2 bytes gathered into 16 lanes x 4 bytes, padding
+                        // columns written as zero so that no sentinel remains in the row
+                        const unsigned lo = (unsigned)__builtin_bit_cast(unsigned short, o);
+                        const unsigned nb = (unsigned)__shfl_down((int)lo, 1, 64);
+                        const unsigned pairw = (n < Lg.N ? lo : 0u) | ((n + 1 < Lg.N ? nb : 0u) << 16);
+                        const bool writer = l < 32 && (l & 1) == 0 && n < Npad;
+                        __builtin_amdgcn_raw_buffer_store_b32(pairw, act,
+                                                              (int)(writer ? Lg.act_off + (unsigned)(m * Npad + n) * 2u : kOob), 0, 16);
+                    }
+                }
+            }
+        }
+
+        // ---- my share of the sentinels for the launch after this one (once, in the first phase)
+        if (ph == 0) {
+            const rsrc_t oa = make_rsrc(other, prev_act);
+            const rsrc_t om = make_rsrc(other + kStackActBytes, prev_mail);
+            const v4u s4 = {kSentinel, kSentinel, kSentinel, kSentinel};
+            for (unsigned v = (unsigned)c * 64u + l; v < (prev_act + 15u) / 16u; v += (unsigned)p.nwg * 64u)
+                store16_agent(oa, v * 16u, s4);
+            for (unsigned v = (unsigned)c * 64u + l; v < (prev_mail + 15u) / 16u; v += (unsigned)p.nwg * 64u)
+                store16_agent(om, v * 16u, s4);
+        }
+    }
+
+    // ---- the last workgroup to get here advances the launch counter and records what was used
+    if (failed && l == 0) __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (l == 0) {
+        const int done = __hip_atomic_fetch_add(p.flags + 5, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == p.nwg - 1) {
+            __hip_atomic_store(p.flags + 5, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.flags + 6, (int)p.act_used, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.flags + 7, (int)p.mail_used, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.flags + 4, (int)(epoch + 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// The launch description travels by value in the kernel arguments.  (Behind a pointer to
+// device memory every field costs a scalar load from memory, which measured 12 % slower; but
+// watch the code object when changing this kernel: indexing the arguments at run-time
+// offsets can make the compiler copy all 4 KiB of them into private memory -- it does with
+// a ring of more than 8 tiles -- and the kernel then crawls.)
+__global__ __launch_bounds__(512) void stack_kernel(const StackParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ Control ctl;
+    const int c = blockIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (w == kStream) service_wave(p, lds, &ctl, c);
+    else streaming_wave(p, lds, &ctl, c);
+}
+
+int g_num_cus = 0;
+constexpr size_t kStackLdsMax = 144 * 1024;
+
+}  // namespace
+
+// Plans one launch over `n` phases starting at `phases[0]`.  The caller has filled M, the
+// phases (x_ext/src_off, K, first_layer, G) and the layers (pointers, N, rank); this fills
+// the exchange offsets, the launch shape and the LDS layout.  False: does not fit this path.
+bool plan_stack(StackParams &p, size_t *lds_bytes)
+{
+    if (g_num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(stack_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStackLdsMax) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+        g_num_cus = n > 0 ? n : 1;
+    }
+    const int M = p.M;
+    int kmax = 0, units_max = 0, jobs_max = 0, hstride_max = 32, gmax = 1;
+    size_t mail = 0;
+    for (int ph = 0; ph < p.nphases; ++ph) {
+        StackPhase &P = p.ph[ph];
+        if (P.K > kmax) kmax = P.K;
+        if (P.G > gmax) gmax = P.G;
+        const int pairs = (P.K + 63) / 64;
+        int nsl = (pairs + 7) / 8;
+        if (nsl > kSplit) nsl = kSplit;
+        if (nsl > 64 / M) nsl = 64 / M;
+        const int pps = (pairs + nsl - 1) / nsl;
+        const int Sn = (pairs + pps - 1) / pps;
+        int units = 0, jobs = 0;
+        P.mail_off = (unsigned)mail;
+        for (int g = 0; g < P.G; ++g) {
+            const StackLayer &L = p.L[P.first_layer + g];
+            units += (L.N + kTileRows - 1) / kTileRows;
+            if (L.rank > 0) {
+                const int hs = h_stride(L.rank);
+                if (hs > hstride_max) hstride_max = hs;
+                jobs += (L.rank + 15) / 16 * Sn;
+                mail += (size_t)Sn * M * hs * 4;
+            }
+        }
+        if (units > units_max) units_max = units;
+        if (jobs > jobs_max) jobs_max = jobs;
+    }
+    if (mail > kStackSetBytes - kStackActBytes) return false;
+    p.mail_used = (unsigned)mail;
+    int nwg = units_max > jobs_max ? units_max : jobs_max;
+    if (nwg > g_num_cus) nwg = g_num_cus;
+    p.nwg = nwg;
+    const int per_wg = (units_max + nwg - 1) / nwg;
+    if (per_wg > kMaxUnits) return false;
+
+    const int kp = round_up(kmax, kTileCols);
+    p.xstride = kp + 16;
+    size_t off = ((size_t)M * p.xstride + 15) & ~size_t(15);     // quantised tokens at offset 0
+    p.xh_off = (int)off;
+    off += ((size_t)M * kmax * 2 + 15) & ~size_t(15);
+    p.tile_off = (int)off;
+    off += (size_t)2 * kMaxUnits * kMaxFusedM * kTileRows * sizeof(int);
+    p.h_off = (int)off;
+    off += (size_t)gmax * M * kHsStride * sizeof(_Float16);
+    off = (off + 1023) & ~size_t(1023);
+    p.unit_off = (int)off;
+    p.unit_alpha = 64 * hstride_max;
+    p.unit_stride = p.unit_alpha + 256;
+    off += (size_t)per_wg * p.unit_stride;
+    *lds_bytes = off;
+    return off <= kStackLdsMax;
+}
+
+hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st)
+{
+    hipLaunchKernelGGL(stack_kernel, dim3(p.nwg), dim3(512), lds_bytes, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace hgf

@@ -99,13 +99,13 @@ def test_few_token_single_launch_parity(M, K, N, r, ws):
         y1, _ = g.check_forward(c["x"])
         after = flags()
         assert after[0] == before[0] + (1 if r % 8 == 0 else 0) and after[1] == 0 and after[2] == 0, (before, after)
-    hb.hgf_set_single_launch(False)
+    hb.hgf_set_single_launch(0)
     try:
         before = flags()
         y2, _ = g.check_forward(c["x"])
         assert np.array_equal(flags(), before)
     finally:
-        hb.hgf_set_single_launch(True)
+        hb.hgf_set_single_launch(2)
     assert_close_fp16(y1, y2.astype(np.float64))
 
 
@@ -181,8 +181,14 @@ def test_config1_stack_teacher_forced(chained, ws):
     with a fresh synthetic input per block so that every linear sees live activations."""
     cases, layers, slots, wiring = _stack_case(1, 1, ws, chained)
     st = hb.Stack(layers, slots, 1)
+    flags = lambda: ws.buf[:32].view(torch.int32).cpu().numpy().copy()
+    before = flags()
     hb.hgf_stack_forward(st, ws)
     torch.cuda.synchronize()
+    after = flags()
+    # the whole list ran as persistent launches over runs of layers (two: 48 layers fit one
+    # launch's description), none of whose bounded waits ran out
+    assert after[4] == before[4] + 2 and after[5] == 0 and after[2] == 0, (before, after)
     host = [s.cpu().numpy() for s in slots]
     live = 0
     for g, (_, _, src, dst) in zip(cases, wiring):
@@ -194,6 +200,21 @@ def test_config1_stack_teacher_forced(chained, ws):
         live += int(np.abs(host[src].astype(np.float32)).max() > 1e-3 and np.abs(ref["acc"]).max() > 100)
     if not chained:
         assert live == len(wiring), live
+    # the same list, one persistent launch per group of layers: the same integers, fp16 within a rounding
+    hb.hgf_set_single_launch(1)
+    try:
+        for (_, _, _, dst) in wiring:
+            slots[dst].zero_()
+        hb.hgf_stack_forward(st, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(flags()[4:8], after[4:8])
+        again = [s.cpu().numpy() for s in slots]
+        if not chained:
+            for (_, _, src, dst) in wiring:
+                if np.array_equal(again[src], host[src]):
+                    assert_close_fp16(again[dst], host[dst].astype(np.float64), f"slot {dst} (per-group launches)")
+    finally:
+        hb.hgf_set_single_launch(2)
     # end of the first block against the oracle's own chain (fp16 hand-over between layers)
     first = [i for i, w in enumerate(wiring) if w[0] == 0]
     chain = orc.stack_forward([{"T": cases[i].T_ref, "s_w": cases[i].s_w_ref, "A": cases[i].case["A"],
@@ -203,6 +224,47 @@ def test_config1_stack_teacher_forced(chained, ws):
     ref_end = chain[end].astype(np.float64)
     rel = np.linalg.norm(host[end].astype(np.float64) - ref_end) / np.linalg.norm(ref_end)
     assert rel < 0.05, rel
+
+
+@pytest.mark.parametrize("M", [1, 3, 4])
+def test_mixed_stack_teacher_forced(M, ws):
+    """A short list that exercises the whole-stack launch and its fall-backs in one call: a
+    group of two layers (one without correction), activations handed on inside the launch,
+    ragged d_in (264), then a layer whose d_out (130) keeps it out of the whole-stack launch
+    and one whose d_in (130) takes the two-launch path.  Every layer is checked against the
+    oracle on the input the GPU gave it; a second run must reproduce the first bit for bit."""
+    shapes = [(256, 512, 16, 0, 1), (256, 384, 0, 0, 2), (512, 256, 32, 1, 3), (256, 264, 8, 3, 4),
+              (264, 128, 24, 4, 5), (128, 130, 16, 5, 6), (130, 64, 8, 6, 7)]
+    cases, layers = [], []
+    slots = [None] * 8
+    for i, (K, N, r, src, dst) in enumerate(shapes):
+        c = synth.make_custom(7000 + 10 * M + i, M, K, N, max(r, 1), act="student_t4", lora_std=0.05, w_std=0.05)
+        if i == 0:
+            slots[0] = dev(c["x"])
+        g = GpuLayer(c, ws, rank0=(r == 0))
+        g.layer.c.src_slot, g.layer.c.dst_slot = src, dst
+        cases.append(g)
+        layers.append(g.layer)
+        slots[dst] = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    st = hb.Stack(layers, slots, M)
+    flags = lambda: ws.buf[:32].view(torch.int32).cpu().numpy().copy()
+    before = flags()
+    hb.hgf_stack_forward(st, ws)
+    torch.cuda.synchronize()
+    after = flags()
+    assert after[4] == before[4] + 1 and after[5] == 0 and after[2] == 0, (before, after)
+    host = [s.cpu().numpy() for s in slots]
+    for g, (K, N, r, src, dst) in zip(cases, shapes):
+        ref = g.oracle(host[src])
+        assert_close_fp16(host[dst], ref["y"], f"slot {dst}")
+        _, acc1 = g.forward(host[src])
+        assert np.array_equal(acc1, ref["acc"])
+    for (_, _, _, _, dst) in shapes:
+        slots[dst].zero_()
+    hb.hgf_stack_forward(st, ws)
+    torch.cuda.synchronize()
+    for (_, _, _, _, dst) in shapes:
+        assert np.array_equal(slots[dst].cpu().numpy(), host[dst])
 
 
 # ------------------------------------------------------------------ full-size configurations, sampled
