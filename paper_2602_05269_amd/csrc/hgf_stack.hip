@@ -488,6 +488,12 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
         __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only: the LDS writes above have landed
         bare_barrier();                 // A: tokens in LDS (and the zeroed counters)
         bare_barrier();                 // B
+        // A read of the staged operands, on every path and before this phase's first store: the
+        // compiler orders it behind the LDS-direct loads (by waiting for all outstanding memory
+        // operations).  Spent here it costs a load's latency; left to the first LDS access
+        // after the stores below, it would cost their acknowledgement -- microseconds while the
+        // weight stream saturates the memory -- at the top of the next phase.
+        asm volatile("" ::"v"(*reinterpret_cast<volatile int *>(ustage)) : "memory");
         // ---- my slices of A x (step 5) while the others quantise
         while (job < njobs) {
             v4f acc = {0.f, 0.f, 0.f, 0.f};
