@@ -24,7 +24,8 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
     ws.rowsum = reinterpret_cast<int32_t *>(take((size_t)M * 4));
-    ws.h16 = reinterpret_cast<_Float16 *>(take((size_t)M * h_stride(rank > 0 ? rank : 1) * 2));
+    ws.h16_each = align256((size_t)M * h_stride(rank > 0 ? rank : 1) * 2);
+    ws.h16 = reinterpret_cast<_Float16 *>(take(ws.h16_each * (M > kMaxDecodeM ? kMaxGroup : 1)));
     // decode: per layer of a group at most 64 (slice, token) rows of h_stride partial sums
     ws.hslices_each = rank > 0 ? align256((size_t)64 * h_stride(rank) * sizeof(float)) : 0;
     ws.hslices = reinterpret_cast<float *>(take(ws.hslices_each * kMaxGroup));
@@ -179,19 +180,31 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     return from_hip(launch_decode(dp, K, st));
 }
 
-// Large M: per layer, quantiser (shared by the group), split down-projection with SiLU,
-// then the int8 MFMA prefill kernel.
-hgf_status run_large_layer(const void *x, int M, const hgf_layer &L, void *y, int32_t *acc_debug,
-                           const Workspace &ws, bool quantise, hipStream_t st)
+// Large M: per group of layers that read the same activations, one quantiser launch, one
+// launch of the down-projections with SiLU (all layers), then the int8 MFMA prefill kernel
+// per layer.
+hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
+                           int32_t *acc_debug, const Workspace &ws, hipStream_t st)
 {
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(x);
-    if (quantise && launch_quantize(xh, M, L.d_in, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess)
-        return HGF_ERR_DEVICE;
-    if (L.rank > 0 &&
-        launch_corr_down(xh, M, L.d_in, reinterpret_cast<const _Float16 *>(L.A_f16), L.rank, ws, st) != hipSuccess)
-        return HGF_ERR_DEVICE;
-    ProfileScope prof(1, st);
-    return from_hip(launch_prefill(ws, M, L, reinterpret_cast<_Float16 *>(y), acc_debug, st));
+    const int K = layers[0].d_in;
+    if (launch_quantize(xh, M, K, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess) return HGF_ERR_DEVICE;
+    const _Float16 *A[kMaxGroup];
+    _Float16 *h16[kMaxGroup];
+    int rank[kMaxGroup];
+    for (int g = 0; g < G; ++g) {
+        A[g] = reinterpret_cast<const _Float16 *>(layers[g].A_f16);
+        rank[g] = layers[g].rank;
+        h16[g] = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
+    }
+    if (launch_corr_down(xh, M, K, G, A, rank, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
+    for (int g = 0; g < G; ++g) {
+        ProfileScope prof(1, st);
+        const hgf_status s = from_hip(launch_prefill(ws, h16[g], M, layers[g], reinterpret_cast<_Float16 *>(ys[g]),
+                                                     acc_debug, st));
+        if (s != HGF_OK) return s;
+    }
+    return HGF_OK;
 }
 
 }  // namespace
@@ -293,7 +306,8 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
         void *ys[1] = {y_f16};
         return run_decode_group(x_f16, M, L, 1, ys, acc_debug, ws, st);
     }
-    return run_large_layer(x_f16, M, *L, y_f16, acc_debug, ws, true, st);
+    void *ys1[1] = {y_f16};
+    return run_large_group(x_f16, M, L, 1, ys1, acc_debug, ws, st);
 }
 
 hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const *slots, int n_slots, int M,
@@ -353,12 +367,9 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
             for (int g = 0; g < gr.G; ++g) ys[g] = slots[layers[gr.first + g].dst_slot];
             return run_decode_group(x, M, layers + gr.first, gr.G, ys, nullptr, ws, st);
         }
-        for (int g = 0; g < gr.G; ++g) {
-            const hgf_layer &L = layers[gr.first + g];
-            const hgf_status s = run_large_layer(x, M, L, slots[L.dst_slot], nullptr, ws, g == 0, st);
-            if (s != HGF_OK) return s;
-        }
-        return HGF_OK;
+        void *ys[kMaxGroup];
+        for (int g = 0; g < gr.G; ++g) ys[g] = slots[layers[gr.first + g].dst_slot];
+        return run_large_group(x, M, layers + gr.first, gr.G, ys, nullptr, ws, st);
     };
 
     // Runs groups [a, b), all stackable, as one persistent launch; false if they do not fit it.

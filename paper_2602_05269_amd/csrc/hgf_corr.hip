@@ -5,7 +5,10 @@
 // fp16 activations, with SiLU(h) = h * sigmoid(h) (Sec. 2.3, low-rank correction).
 // A skinny GEMM on the 32x32x16 f16 MFMA: matrix rows are rank indices (so a lane ends up
 // with four consecutive ranks of one token: 8-byte stores), matrix columns are tokens.
-// One workgroup of four wavefronts owns 32 tokens.  x and A are streamed through LDS in
+// One workgroup of four wavefronts owns 32 tokens and one tile of 32 ranks of one layer
+// (blockIdx.y walks the rank tiles of every layer of the group: all layers that read the same
+// activations share one launch, which fills the chip where a single layer's 64 token tiles
+// would not).  x and A are streamed through LDS in
 // stretches of KC columns with LDS-direct loads (whole row pieces, coalesced; double
 // buffered, requested one stretch ahead); each wavefront multiplies a quarter of the stretch
 // for every rank tile; the four partial tiles meet in LDS at the end and the first
@@ -18,10 +21,16 @@ namespace {
 
 struct CorrParams {
     const _Float16 *x;
-    const _Float16 *A;
+    const _Float16 *A;                          // the layer of a ragged launch; of a grouped launch: A4[g]
     _Float16 *h16;
     int M, K, rank, hstride;
     int steps;                                  // stretches of KC columns
+    // grouped launch: blockIdx.y walks the 32-rank tiles of up to four layers that read the same x
+    int G;
+    const _Float16 *A4[kMaxGroup];
+    _Float16 *h4[kMaxGroup];
+    int rank4[kMaxGroup], hstride4[kMaxGroup];
+    int tile_start[kMaxGroup + 1];
 };
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -48,8 +57,17 @@ __global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m0 = blockIdx.x * 32;
     const int mrows = min(32, p.M - m0);
+    // this workgroup's layer and first rank (RT tiles of 32 from there)
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i)
+        if (i < p.G && (int)blockIdx.y >= p.tile_start[i]) g = i;
+    const int j_first = ((int)blockIdx.y - p.tile_start[g]) * 32 * RT;
+    const int rank = p.rank4[g], hstride = p.hstride4[g];
+    _Float16 *const h16 = p.h4[g];
+    const int arows = min(RT * 32, rank - j_first);          // rows of A this workgroup reads (may be <= 0)
     const rsrc_t xr = make_rsrc(p.x + (size_t)m0 * p.K, (unsigned)mrows * p.K * 2u);
-    const rsrc_t ar = make_rsrc(p.A, (unsigned)p.rank * p.K * 2u);
+    const rsrc_t ar = make_rsrc(p.A4[g] + (size_t)j_first * p.K, arows > 0 ? (unsigned)arows * p.K * 2u : 0u);
 
     // Staging: one instruction moves 1 KiB = kRowsPerInst rows; lane L writes row
     // kRowsPerInst*ii + L/kPieces, slot L%kPieces.  Rows beyond the last token / rank lie
@@ -144,15 +162,15 @@ __global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
     // acc[rt][4q+v]: rank rt*32 + 8q + 4hf + v of token m0 + jl
     const int m = m0 + jl;
     if (m >= p.M) return;
-    _Float16 *hrow = p.h16 + (size_t)m * p.hstride;
+    _Float16 *hrow = h16 + (size_t)m * hstride;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int j0 = rt * 32 + 8 * q + 4 * hf;
+            const int j0 = j_first + rt * 32 + 8 * q + 4 * hf;
             v4h o;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] = (j0 + v < p.rank) ? (_Float16)silu(acc[rt][4 * q + v]) : (_Float16)0.0f;
+            for (int v = 0; v < 4; ++v) o[v] = (j0 + v < rank) ? (_Float16)silu(acc[rt][4 * q + v]) : (_Float16)0.0f;
             *reinterpret_cast<v4h *>(hrow + j0) = o;
         }
     }
@@ -176,38 +194,42 @@ __global__ __launch_bounds__(256) void corr_down_ragged_kernel(CorrParams p)
 
 }  // namespace
 
-hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, int rank, const Workspace &ws,
-                            hipStream_t st)
+// Layers 0..G-1 read the same x; layer g's result goes to h16[g] ([M, h_stride(rank[g])] fp16).
+hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
+                            _Float16 *const *h16, hipStream_t st)
 {
     CorrParams p;
     p.x = x;
-    p.A = A;
-    p.h16 = ws.h16;
     p.M = M;
     p.K = K;
-    p.rank = rank;
-    p.hstride = h_stride(rank);
-    const bool vec = (K % 8 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(A)) % 16 == 0);
+    bool vec = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+    for (int g = 0; g < G; ++g) vec = vec && (rank[g] == 0 || reinterpret_cast<uintptr_t>(A[g]) % 16 == 0);
     if (!vec) {
-        const size_t n = (size_t)M * p.hstride;
-        hipLaunchKernelGGL(corr_down_ragged_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+        for (int g = 0; g < G; ++g) {
+            if (rank[g] == 0) continue;
+            p.A = A[g];
+            p.h16 = h16[g];
+            p.rank = rank[g];
+            p.hstride = h_stride(rank[g]);
+            const size_t n = (size_t)M * p.hstride;
+            hipLaunchKernelGGL(corr_down_ragged_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+        }
         return hipGetLastError();
     }
-    const dim3 grid((M + 31) / 32), block(256);
-    switch (p.hstride / 32) {               // rank tiles cover the padded row: every column is written
-        case 1:
-            p.steps = (K + 255) / 256;
-            hipLaunchKernelGGL((corr_down_kernel<1, 256>), grid, block, 0, st, p);
-            break;
-        case 2:
-            p.steps = (K + 255) / 256;
-            hipLaunchKernelGGL((corr_down_kernel<2, 256>), grid, block, 0, st, p);
-            break;
-        default:
-            p.steps = (K + 127) / 128;
-            hipLaunchKernelGGL((corr_down_kernel<4, 128>), grid, block, 0, st, p);
-            break;
+    int tiles = 0;
+    p.G = G;
+    for (int g = 0; g < kMaxGroup; ++g) {
+        p.tile_start[g] = tiles;
+        p.A4[g] = g < G ? A[g] : nullptr;
+        p.h4[g] = g < G ? h16[g] : nullptr;
+        p.rank4[g] = g < G ? rank[g] : 0;
+        p.hstride4[g] = g < G ? h_stride(rank[g]) : 32;
+        if (g < G && rank[g] > 0) tiles += p.hstride4[g] / 32;     // tiles cover the padded row: every column is written
     }
+    p.tile_start[kMaxGroup] = tiles;
+    if (tiles == 0) return hipSuccess;
+    p.steps = (K + 255) / 256;
+    hipLaunchKernelGGL((corr_down_kernel<1, 256>), dim3((M + 31) / 32, tiles), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

@@ -128,7 +128,8 @@ struct Workspace {
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
-    _Float16 *h16;       // large M: [M, h_stride] SiLU(A x), zero padded
+    _Float16 *h16;       // large M: kMaxGroup x [M, h_stride] SiLU(A x), zero padded (one per layer of a group)
+    size_t h16_each;     // bytes per layer
     float *hslices;      // decode: kMaxGroup x [S, M, h_stride] fp32 partial sums of A x
     size_t hslices_each; // bytes per layer of a group
     double *wsum;        // [kWsumBlocks]
@@ -256,8 +257,8 @@ hipError_t launch_unpack(const uint32_t *packed, int N, int K, int8_t *T, hipStr
 hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st);
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st);
-hipError_t launch_corr_down(const _Float16 *x, int M, int K, const _Float16 *A, int rank,
-                            const Workspace &ws, hipStream_t st);
+hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
+                            _Float16 *const *h16, hipStream_t st);
 int prologue_slices(int M, int K);
 hipError_t launch_prologue(ProParams &p, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
@@ -267,7 +268,7 @@ int decode_target_waves();
 bool plan_stack(StackParams &p, size_t *lds_bytes);
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
 void set_decode_target_wgs(int v);
-hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
-                          hipStream_t st);
+hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const hgf_layer &L, _Float16 *y,
+                          int32_t *acc_debug, hipStream_t st);
 
 }  // namespace hgf

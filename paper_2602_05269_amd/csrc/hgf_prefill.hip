@@ -294,8 +294,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 
 }  // namespace
 
-hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float16 *y, int32_t *acc_debug,
-                          hipStream_t st)
+hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const hgf_layer &L, _Float16 *y,
+                          int32_t *acc_debug, hipStream_t st)
 {
     PrefillParams p;
     p.packed = reinterpret_cast<const v4u *>(L.W_packed);
@@ -305,7 +305,7 @@ hipError_t launch_prefill(const Workspace &ws, int M, const hgf_layer &L, _Float
     p.s_w = L.s_w;
     p.B = reinterpret_cast<const _Float16 *>(L.B_f16);
     p.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-    p.h16 = ws.h16;
+    p.h16 = h16;
     p.y = y;
     p.acc_debug = acc_debug;
     p.M = M;

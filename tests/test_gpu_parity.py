@@ -226,13 +226,15 @@ def test_config1_stack_teacher_forced(chained, ws):
     assert rel < 0.05, rel
 
 
-@pytest.mark.parametrize("M", [1, 3, 4])
+@pytest.mark.parametrize("M", [1, 3, 4, 70])
 def test_mixed_stack_teacher_forced(M, ws):
     """A short list that exercises the whole-stack launch and its fall-backs in one call: a
     group of two layers (one without correction), activations handed on inside the launch,
     ragged d_in (264), then a layer whose d_out (130) keeps it out of the whole-stack launch
     and one whose d_in (130) takes the two-launch path.  Every layer is checked against the
-    oracle on the input the GPU gave it; a second run must reproduce the first bit for bit."""
+    oracle on the input the GPU gave it; a second run must reproduce the first bit for bit.
+    M = 70 sends the same list down the prefill path, whose down-projection kernel serves
+    both layers of the group in one launch."""
     shapes = [(256, 512, 16, 0, 1), (256, 384, 0, 0, 2), (512, 256, 32, 1, 3), (256, 264, 8, 3, 4),
               (264, 128, 24, 4, 5), (128, 130, 16, 5, 6), (130, 64, 8, 6, 7)]
     cases, layers = [], []
@@ -252,7 +254,7 @@ def test_mixed_stack_teacher_forced(M, ws):
     hb.hgf_stack_forward(st, ws)
     torch.cuda.synchronize()
     after = flags()
-    assert after[4] == before[4] + 1 and after[5] == 0 and after[2] == 0, (before, after)
+    assert after[4] == before[4] + (1 if M <= 4 else 0) and after[5] == 0 and after[2] == 0, (before, after)
     host = [s.cpu().numpy() for s in slots]
     for g, (K, N, r, src, dst) in zip(cases, shapes):
         ref = g.oracle(host[src])
