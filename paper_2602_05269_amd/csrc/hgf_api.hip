@@ -25,9 +25,10 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
     ws.rowsum = reinterpret_cast<int32_t *>(take((size_t)M * 4));
     ws.h16_each = align256((size_t)M * h_stride(rank > 0 ? rank : 1) * 2);
-    ws.h16 = reinterpret_cast<_Float16 *>(take(ws.h16_each * (M > kMaxDecodeM ? kMaxGroup : 1)));
-    // decode: per layer of a group at most 64 (slice, token) rows of h_stride partial sums
-    ws.hslices_each = rank > 0 ? align256((size_t)64 * h_stride(rank) * sizeof(float)) : 0;
+    ws.h16 = reinterpret_cast<_Float16 *>(take(ws.h16_each * kMaxGroup));
+    // two-launch decode path: per layer of a group kMaxHSplit slices of [M, h_stride] partial sums
+    const int Md = M < kMaxDecodeM ? M : kMaxDecodeM;
+    ws.hslices_each = rank > 0 ? align256((size_t)kMaxHSplit * Md * h_stride(rank) * sizeof(float)) : 0;
     ws.hslices = reinterpret_cast<float *>(take(ws.hslices_each * kMaxGroup));
     ws.wsum = reinterpret_cast<double *>(take(size_t(kWsumBlocks) * 8));
     (void)d_out;
@@ -124,7 +125,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
             D.s_w = L.s_w;
             D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
             D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-            D.hpart = nullptr;
+            D.h16 = nullptr;
             D.y = reinterpret_cast<_Float16 *>(ys[g]);
             D.acc_debug = acc_debug;
             D.N = L.d_out;
@@ -166,7 +167,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         D.s_w = L.s_w;
         D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
         D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-        D.hpart = slices;
+        D.h16 = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
         D.y = reinterpret_cast<_Float16 *>(ys[g]);
         D.acc_debug = acc_debug;
         D.N = L.d_out;
@@ -174,8 +175,9 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         D.rank = L.rank;
         D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
     }
-    if (launch_prologue(pp, st) != hipSuccess) return HGF_ERR_DEVICE;
-    dp.S = pp.S;
+    _Float16 *h16[kMaxGroup];
+    for (int g = 0; g < G; ++g) h16[g] = const_cast<_Float16 *>(dp.L[g].h16);
+    if (launch_prologue(pp, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
     ProfileScope prof(0, st);
     return from_hip(launch_decode(dp, K, st));
 }

@@ -59,18 +59,14 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     const int n0 = rb * kTileRows;                   // this wavefront's 32 output rows
     const bool owner = rb_ok && kw == 0;             // runs the epilogue of the row-block
 
-    // ---- (1) partial sums of A x for the first element this thread turns into SiLU(A x)
-    const rsrc_t hr = make_rsrc(L.hpart, L.rank > 0 ? (unsigned)p.S * p.M * L.hstride * 4u : 0u);
+    // ---- (1) SiLU(A x) of the tokens, fp16 rows of hstride (a small kernel has added the slices
+    //      of the prologue): 16 bytes per thread and request
+    constexpr int HV = 2;                            // 512 x 2 x 8 halves >= 64 tokens x 128 ranks
     const int htotal = L.rank > 0 ? mcount * L.hstride : 0;
-    float hpre[kMaxHSplit];
-    {
-        const int m = tid / L.hstride, j = tid - m * L.hstride;
-        const bool ok = tid < htotal && j < L.rank;
-        const unsigned row = (unsigned)m * L.hstride + j;
+    const rsrc_t hr = make_rsrc(L.h16, (unsigned)htotal * 2u);
+    v4u hpre[HV];
 #pragma unroll
-        for (int sp = 0; sp < kMaxHSplit; ++sp)
-            hpre[sp] = __builtin_bit_cast(float, buf_load4(hr, (row + (unsigned)sp * p.M * L.hstride) * 4u, ok && sp < p.S));
-    }
+    for (int u = 0; u < HV; ++u) hpre[u] = buf_load16(hr, (unsigned)(tid + u * nthreads) * 16u, (tid + u * nthreads) * 8 < htotal);
 
     // ---- (2) the first pieces of the quantised activations (16 bytes each)
     const int cend0 = min(p.CT, p.KT);
@@ -132,28 +128,14 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
         for (int t = 0; t < PF; ++t) wq[t] = buf_load16_stream(wr, (unsigned)(kt0 + t * p.KW) * kTileBytes + l * 16);
     }
 
-    // ---- SiLU(A x) of the tokens (fp16 rows of hstride) and tanh(alpha) into LDS
+    // ---- SiLU(A x) of the tokens and tanh(alpha) into LDS
     _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off);
     float *gs = reinterpret_cast<float *>(lds + p.g_off);
-    if (tid < htotal) {
-        float h = hpre[0];
 #pragma unroll
-        for (int sp = 1; sp < kMaxHSplit; ++sp) h += hpre[sp];       // slice order: deterministic
-        hs[tid] = (_Float16)silu(h);
-    }
-    for (int idx = tid + nthreads; idx < htotal; idx += nthreads) {  // M*hstride > workgroup size
-        const int m = idx / L.hstride, j = idx - m * L.hstride;
-        const unsigned row = (unsigned)m * L.hstride + j;
-        float part[kMaxHSplit];
-#pragma unroll
-        for (int sp = 0; sp < kMaxHSplit; ++sp)
-            part[sp] = __builtin_bit_cast(float, buf_load4(hr, (row + (unsigned)sp * p.M * L.hstride) * 4u,
-                                                           j < L.rank && sp < p.S));
-        float h = 0.f;
-#pragma unroll
-        for (int sp = 0; sp < kMaxHSplit; ++sp) h += part[sp];
-        hs[idx] = (_Float16)silu(h);
-    }
+    for (int u = 0; u < HV; ++u)
+        if ((tid + u * nthreads) * 8 < htotal) *reinterpret_cast<v4u *>(hs + (tid + u * nthreads) * 8) = hpre[u];
+    for (int v = tid + HV * nthreads; v * 8 < htotal; v += nthreads)   // workgroups of 256 threads, many tokens
+        *reinterpret_cast<v4u *>(hs + v * 8) = buf_load16(hr, (unsigned)v * 16u);
     if (tid < p.RW * kTileRows) gs[tid] = L.rank > 0 ? tanhf(alpha_pre) : 0.f;
 
     v16i acc[TG];
@@ -182,10 +164,22 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
                 }
                 first = XPRE * nthreads;
             }
-            for (int pc = first + tid; pc < total; pc += nthreads) {
-                const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
-                const v4u v = buf_load16(xr, (unsigned)row * p.Kp + (unsigned)c0 * kTileCols + col * 16);
-                *reinterpret_cast<v4u *>(lds + row * p.xstride + col * 16) = v;
+            // the rest in batches of eight requests (one at a time would pay a memory round trip
+            // per piece: the time of this kernel would grow with the number of tokens)
+            for (int pc0 = first + tid; pc0 < total; pc0 += 8 * nthreads) {
+                v4u v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int pc = pc0 + u * nthreads;
+                    const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
+                    v[u] = buf_load16(xr, (unsigned)row * p.Kp + (unsigned)c0 * kTileCols + col * 16, pc < total);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int pc = pc0 + u * nthreads;
+                    const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
+                    if (pc < total) *reinterpret_cast<v4u *>(lds + row * p.xstride + col * 16) = v[u];
+                }
             }
         }
         __syncthreads();
@@ -292,7 +286,7 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 }
 
 int g_target_waves = 2048;
-constexpr int kDecodeLdsBudget = 64 * 1024;
+constexpr int kDecodeLdsBudget = 144 * 1024;   // one workgroup of 512 threads per compute unit anyway
 
 }  // namespace
 
@@ -341,6 +335,15 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
     p.g_off = (int)(stage + ((hbytes + 15) & ~size_t(15)));
     const size_t lds = p.g_off + gbytes;
 
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    static const hipError_t attr = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<2>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    }();
+    if (attr != hipSuccess) return attr;
     const dim3 grid(wgs), block(64 * nwaves);
     if (tgroups == 1)
         hipLaunchKernelGGL(decode_kernel<1>, grid, block, lds, st, p);

@@ -176,7 +176,7 @@ struct DecLayer {
     const float *s_w;
     const _Float16 *B;
     const _Float16 *alpha;
-    const float *hpart;      // [S, M, hstride] fp32 partial sums of A x from the prologue
+    const _Float16 *h16;     // [M, hstride] fp16 SiLU(A x) (two-launch path), zero padded
     _Float16 *y;
     int32_t *acc_debug;
     int N, RBn, rank, hstride;
@@ -190,7 +190,6 @@ struct DecodeParams {
     int wg_start[kMaxGroup + 1];
     int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4 or 8)
     int CT, xstride;         // tiles of d_in staged in LDS at a time; bytes per staged row
-    int S;                   // slices of the correction partial sums
     int h_off, g_off;        // byte offsets in LDS of the SiLU(A x) rows and of the tanh(alpha) table
 };
 
@@ -205,7 +204,7 @@ constexpr size_t kMailBytes = kMailLayerBytes * kMaxGroup;    // one exchange bu
 struct FusedParams {
     const _Float16 *x;            // [M, K] fp16
     int M, K, Kp, KT, TPW, G;     // TPW: tiles of a unit per streaming wavefront
-    DecLayer L[kMaxGroup];        // hpart unused
+    DecLayer L[kMaxGroup];        // h16 unused
     const _Float16 *A[kMaxGroup];
     int ustart[kMaxGroup + 1];    // running sum of the layers' row-blocks
     int job_start[kMaxGroup + 1]; // running sum of the layers' (rank tile, slice) jobs
@@ -260,7 +259,7 @@ hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
                             _Float16 *const *h16, hipStream_t st);
 int prologue_slices(int M, int K);
-hipError_t launch_prologue(ProParams &p, hipStream_t st);
+hipError_t launch_prologue(ProParams &p, _Float16 *const *h16, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
 bool plan_fused(FusedParams &p, size_t *lds_bytes);
 hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);

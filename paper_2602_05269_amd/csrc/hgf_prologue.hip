@@ -174,21 +174,50 @@ __global__ __launch_bounds__(256) void prologue_kernel(ProParams p)
     if (job < p.job_start[p.G]) corr_partial<TT, VEC>(p, job);
 }
 
+// Adds the slices in order (deterministic), applies SiLU (Alg. 1 step 6) and writes fp16 rows of
+// hstride (zero padded): one thread per (layer, token, rank), all its slices requested at once.
+struct ReduceParams {
+    const float *hpart[kMaxGroup];
+    _Float16 *h16[kMaxGroup];
+    int rank[kMaxGroup], rp[kMaxGroup], start[kMaxGroup + 1];
+    int M, S, G;
+};
+__global__ __launch_bounds__(256) void hreduce_kernel(ReduceParams p)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i)
+        if (i < p.G && e >= p.start[i]) g = i;
+    const int idx = e - p.start[g], rp = p.rp[g];
+    const bool inside = e < p.start[p.G];
+    const int j = idx % rp;
+    const rsrc_t hr = make_rsrc(p.hpart[g], (unsigned)p.S * p.M * rp * 4u);
+    float part[kMaxHSplit];
+#pragma unroll
+    for (int sp = 0; sp < kMaxHSplit; ++sp)
+        part[sp] = __builtin_bit_cast(float, buf_load4(hr, ((unsigned)idx + (unsigned)sp * p.M * rp) * 4u,
+                                                       inside && j < p.rank[g] && sp < p.S));
+    float h = part[0];
+#pragma unroll
+    for (int sp = 1; sp < kMaxHSplit; ++sp) h += part[sp];
+    if (inside) p.h16[g][idx] = (_Float16)silu(h);
+}
+
 }  // namespace
 
 int prologue_slices(int M, int K)
 {
     const int pairs = (K + 63) / 64;
     int s = (pairs + 7) / 8;                   // 512 columns per slice: one batch of loads
-    const int cap = 64 / M > 1 ? 64 / M : 1;   // the consumer adds S*M*rank partial sums
-    if (s > cap) s = cap;
+    (void)M;
     if (s > kMaxHSplit) s = kMaxHSplit;
     if (s < 1) s = 1;
     const int per = (pairs + s - 1) / s;
     return (pairs + per - 1) / per;
 }
 
-hipError_t launch_prologue(ProParams &p, hipStream_t st)
+hipError_t launch_prologue(ProParams &p, _Float16 *const *h16, hipStream_t st)
 {
     p.pairs = (p.K + 63) / 64;
     p.S = prologue_slices(p.M, p.K);
@@ -216,6 +245,22 @@ hipError_t launch_prologue(ProParams &p, hipStream_t st)
         default: HGF_PRO(4); break;
     }
 #undef HGF_PRO
+    ReduceParams rp;
+    rp.M = p.M;
+    rp.S = p.S;
+    rp.G = p.G;
+    int total = 0;
+    for (int g = 0; g < kMaxGroup; ++g) {
+        rp.start[g] = total;
+        rp.hpart[g] = g < p.G ? p.L[g].hpart : nullptr;
+        rp.h16[g] = g < p.G ? h16[g] : nullptr;
+        rp.rank[g] = g < p.G ? p.L[g].rank : 0;
+        rp.rp[g] = g < p.G ? p.L[g].rp : 32;
+        if (g < p.G && p.L[g].rank > 0) total += p.M * p.L[g].rp;
+    }
+    rp.start[kMaxGroup] = total;
+    for (int g = p.G; g <= kMaxGroup; ++g) rp.start[g] = total;
+    if (total > 0) hipLaunchKernelGGL(hreduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, rp);
     return hipGetLastError();
 }
 
