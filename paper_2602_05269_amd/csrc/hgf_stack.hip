@@ -8,9 +8,13 @@
 //
 //   * seven streaming wavefronts keep a ring of weight tiles in flight across phase
 //     boundaries: weights do not depend on activations, so while a phase waits for its input
-//     the memory system keeps delivering its first tiles;
-//   * one service wavefront fetches the phase's input, computes its slice of A x, collects
-//     all slices, and finishes the units its workgroup owns (dequantise, B h, gate, store).
+//     the memory system keeps delivering its first tiles.  Wavefront w contracts the k-tiles
+//     w, w+7, ... of every row-block, so it fetches and quantises exactly those columns of the
+//     tokens itself; the seven meet once per phase, for the per-token absmax;
+//   * one service wavefront computes its slice of A x from the columns that slice needs,
+//     collects all slices, and finishes the units its workgroup owns (dequantise, B h, gate,
+//     store).  It shares no barrier with the streaming side: the two meet through counters
+//     in LDS.
 //
 // Activations pass from one phase to the next through the workspace: the service wavefronts
 // store every output both to the caller's slot and, with device scope, to an exchange
@@ -21,16 +25,13 @@
 // alternate from launch to launch by a counter in the workspace; each launch refills, in the
 // other set, what the previous launch used.  Every wait is bounded; on expiry a sticky word
 // is set in the workspace, the affected outputs are NaN and later waits are skipped.
-//
-// Inside a workgroup the two sides meet at three barriers per phase (input in LDS; absmax;
-// quantised input in LDS) and through LDS counters per unit.
 #include "hgf_internal.h"
 
 namespace hgf {
 
 namespace {
 
-constexpr int kStream = 7;             // streaming wavefronts per workgroup (wavefront 7 is the service one)
+constexpr int kStream = 6;             // streaming wavefronts per workgroup (wavefronts 6 and 7 serve them)
 #ifndef HGF_STACK_PF
 #define HGF_STACK_PF 8
 #endif
@@ -46,11 +47,15 @@ constexpr int kSplit = kFusedSplit;    // slices of d_in at most
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
-struct Control {                       // LDS words shared by the two sides, one set per phase parity
-    int arrived[2][kMaxUnits];         // streaming wavefronts that have posted the unit
-    int rowsum[2][kMaxFusedM];
-    float amax_part[kStream][kMaxFusedM];
+struct Control {                       // LDS words shared by the two sides; [2]: one set per phase parity
+    int arrived[2][kMaxUnits];         // streaming wavefronts that have posted the unit (the service side resets it)
+    int rowsum_part[2][kStream][kMaxFusedM];   // sums of the quantised columns each wavefront owns
+    float amax_part[2][kStream][kMaxFusedM];   // absmax of those columns
     float sx[2][kMaxFusedM];
+    int sync;                          // absmax parts posted, summed over the phases
+    int svc_done;                      // phases whose units the unit wavefront has finished
+    int h_ready;                       // phases whose SiLU(A x) the slice wavefront has put into LDS
+    int failed;                        // a wait of the streaming side has expired
 };
 
 __device__ __forceinline__ int lds_load(const int *p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
@@ -69,13 +74,6 @@ __device__ __forceinline__ bool has_sentinel(v4u v)
 __device__ __forceinline__ float exp_fast(float v) { return __builtin_amdgcn_exp2f(v * 1.44269504088896340736f); }
 __device__ __forceinline__ float silu_fast(float h) { return h * __builtin_amdgcn_rcpf(1.0f + exp_fast(-h)); }
 __device__ __forceinline__ float tanh_fast(float a) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_fast(2.0f * a)); }
-__device__ __forceinline__ void bare_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 // What both sides derive from a phase's entry in the kernel arguments (all wave-uniform).
 struct PhaseShape {
     int K, Kp, KT, TPW, G, first;      // first: index of the phase's first layer
@@ -112,12 +110,100 @@ __device__ __forceinline__ int ring_steps(const PhaseShape &s)
 }
 
 // ------------------------------------------------------------------ streaming side
+// Per-token absmax int8 quantisation (Sec. 2.2.1) of the columns wavefront w contracts: the
+// k-tiles w, w+7, ... (128 columns each).  The columns come from the caller's slot or, once
+// no word of them is the sentinel, from the exchange region; they stay in registers between
+// the two passes.  The seven wavefronts exchange their absmax parts through LDS and a counter
+// (`sync_target`: its value once all seven have posted this phase's part); the quantised
+// columns go to the token rows in LDS, where only this wavefront reads them.
+template <int MT>
+__device__ __forceinline__ void fetch_quantise(const StackParams &p, const PhaseShape &S, rsrc_t xr, bool ext,
+                                               unsigned char *lds, Control *ctl, int w, int ph, int sync_target,
+                                               bool &failed)
+{
+    const int l = threadIdx.x & 63, par = ph & 1;
+    constexpr int XU = 4;               // 64 lanes x 4 pieces of 8 columns >= 14 tiles of a token
+    const int pc = l & 15;
+    v4u v[MT][XU];
+    int polls = 0;
+    while (true) {
+        bool ready = true;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+#pragma unroll
+            for (int u = 0; u < XU; ++u) {
+                const int j = (l >> 4) + 4 * u;
+                const int col = (j * kStream + w) * kTileCols + pc * 8;
+                v[m][u] = load16_agent(xr, (unsigned)(m * S.K + col) * 2u, m < p.M && j < S.TPW && col < S.K);
+                ready = ready && !has_sentinel(v[m][u]);
+            }
+        }
+        if (ext || failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
+        if (++polls >= kMemPolls) {
+            failed = true;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        float amax = 0.0f;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const v8h a = __builtin_elementwise_abs(__builtin_bit_cast(v8h, v[m][u]));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, (float)a[e]);
+        }
+        amax = wave_max(amax);
+        if (l == 0) ctl->amax_part[par][w][m] = amax;
+    }
+    if (l == 0) __hip_atomic_fetch_add(&ctl->sync, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    polls = 0;
+    while (!failed && lds_load(&ctl->sync) < sync_target) {
+        if (++polls >= kLdsPolls) failed = true;
+    }
+    // what this phase shares with the service side was last used two phases ago
+    polls = 0;
+    while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
+        if (++polls >= kLdsPolls) failed = true;
+        __builtin_amdgcn_s_sleep(1);
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        float amax = ctl->amax_part[par][0][m];
+#pragma unroll
+        for (int i = 1; i < kStream; ++i) amax = fmaxf(amax, ctl->amax_part[par][i][m]);
+        amax = fmaxf(amax, 1e-5f);
+        const float inv = 127.0f / amax;
+        int sum = 0;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int j = (l >> 4) + 4 * u;
+            const int kt = j * kStream + w;
+            const v8h x8 = __builtin_bit_cast(v8h, v[m][u]);        // columns past d_in were read as zero
+            uint32_t q2[2] = {0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int q = quant1((float)x8[e], inv);
+                sum += q;
+                q2[e >> 2] |= (uint32_t)(q & 0xff) << (8 * (e & 3));
+            }
+            if (m < p.M && j < S.TPW && kt < S.KT)
+                *reinterpret_cast<uint2 *>(lds + m * p.xstride + kt * kTileCols + pc * 8) = make_uint2(q2[0], q2[1]);
+        }
+        sum = wave_sum(sum);
+        if (l == 0 && m < p.M) {
+            ctl->rowsum_part[par][w][m] = sum;
+            if (w == 0) ctl->sx[par][m] = amax / 127.0f;
+        }
+    }
+}
+
 __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
 {
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int jl = l & 31, hf = l >> 5;
-    constexpr int nthreads = kStream * 64;
 
     // ---- load cursor: phase lp, step ls of its padded ring sequence (unit li, tile lj)
     int lp = 0, ls = 0, li = 0, lj = 0, lsteps = 0;
@@ -179,53 +265,26 @@ __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned ch
 #pragma unroll
     for (int t = 0; t < kPF; ++t) issue(wq[t]);
 
-    const _Float16 *xh = reinterpret_cast<const _Float16 *>(lds + p.xh_off);
+    const unsigned epoch = (unsigned)__hip_atomic_load(p.flags + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
+    bool failed = false;
+    int sync_target = 0;
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
         const int par = ph & 1;
-        bare_barrier();                 // A: the service wavefront has put the phase's tokens (fp16) into LDS
-        // ---- per-token absmax int8 quantisation into LDS (Sec. 2.2.1)
         if (S.nunits > 0) {
-            for (int m = 0; m < p.M; ++m) {
-                float amax = 0.0f;
-                for (int i = tid; i < S.K / 8; i += nthreads) {
-                    const v8h a = __builtin_elementwise_abs(*reinterpret_cast<const v8h *>(xh + (size_t)m * S.K + i * 8));
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, (float)a[e]);
-                }
-                amax = wave_max(amax);
-                if (l == 0) ctl->amax_part[w][m] = amax;
-            }
+            const StackPhase &P = p.ph[ph];
+            const bool ext = P.x_ext != nullptr;
+            const rsrc_t xr = make_rsrc(ext ? reinterpret_cast<const unsigned char *>(P.x_ext) : mine + P.src_off,
+                                        (unsigned)p.M * S.K * 2u);
+            sync_target += kStream;
+            if (lds_load(&ctl->failed) != 0) failed = true;
+            const bool was = failed;
+            if (p.M == 1) fetch_quantise<1>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
+            else if (p.M == 2) fetch_quantise<2>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
+            else fetch_quantise<4>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
+            if (failed && !was && l == 0) __hip_atomic_store(&ctl->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
-        __syncthreads();                // B: every wavefront's part of the absmax
-        if (S.nunits > 0) {
-            for (int m = 0; m < p.M; ++m) {
-                float amax = ctl->amax_part[0][m];
-#pragma unroll
-                for (int i = 1; i < kStream; ++i) amax = fmaxf(amax, ctl->amax_part[i][m]);
-                amax = fmaxf(amax, 1e-5f);
-                const float inv = 127.0f / amax;
-                int sum = 0;
-                for (int i = tid; i < S.Kp / 8; i += nthreads) {
-                    v8h v = {0, 0, 0, 0, 0, 0, 0, 0};
-                    if (i < S.K / 8) v = *reinterpret_cast<const v8h *>(xh + (size_t)m * S.K + i * 8);
-                    uint32_t q2[2] = {0u, 0u};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int q = quant1((float)v[e], inv);
-                        sum += q;
-                        q2[e >> 2] |= (uint32_t)(q & 0xff) << (8 * (e & 3));
-                    }
-                    *reinterpret_cast<uint2 *>(lds + m * p.xstride + i * 8) = make_uint2(q2[0], q2[1]);
-                }
-                sum = wave_sum(sum);
-                if (l == 0) {
-                    __hip_atomic_fetch_add(&ctl->rowsum[par][m], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (w == 0) ctl->sx[par][m] = amax / 127.0f;
-                }
-            }
-        }
-        __syncthreads();                // C: the quantised tokens are in LDS
 
         // ---- contraction: one ring slot per step.  Straight-line code: the refill of a slot is
         //      unconditional and the loop has no inner loop (either would cost the ring its
@@ -295,20 +354,39 @@ __device__ __forceinline__ void job_load(JobRegs &r, const _Float16 *A, int rank
         r.a[u][1] = buf_load8h<true>(ar, (unsigned)j * K + k0 + 8, K - k0 - 8, ok);
     }
 }
-// The tokens' side comes from the fp16 copy in LDS.
-__device__ __forceinline__ v4f job_mfma(const JobRegs &r, const _Float16 *xh, int M, int K, int kpb, int kp1, v4f acc)
+// The tokens' side of the same batch: lane (i, kb) holds token i's 16 columns at 64*kp + 16*kb,
+// read from the caller's slot or, once no word is the sentinel, from the exchange region.
+struct JobX {
+    v4u b[kUN][2];
+};
+__device__ __forceinline__ void job_xload(JobX &x, rsrc_t xr, bool ext, int M, int K, int kpb, int kp1, bool &failed)
 {
     const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
+    int polls = 0;
+    while (true) {
+        bool ready = true;
+#pragma unroll
+        for (int u = 0; u < kUN; ++u) {
+            const int k0 = (kpb + u) * 64 + kb * 16;
+            const bool ok = i < M && (kpb + u) < kp1;
+            x.b[u][0] = load16_agent(xr, (unsigned)(i * K + k0) * 2u, ok && k0 < K);
+            x.b[u][1] = load16_agent(xr, (unsigned)(i * K + k0 + 8) * 2u, ok && k0 + 8 < K);
+            ready = ready && !has_sentinel(x.b[u][0]) && !has_sentinel(x.b[u][1]);
+        }
+        if (ext || failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
+        if (++polls >= kMemPolls) {
+            failed = true;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
+__device__ __forceinline__ v4f job_mfma(const JobRegs &r, const JobX &x, v4f acc)
+{
 #pragma unroll
     for (int u = 0; u < kUN; ++u) {
-        const int k0 = (kpb + u) * 64 + kb * 16;
-        v8h b0 = {0, 0, 0, 0, 0, 0, 0, 0}, b1 = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (i < M && (kpb + u) < kp1) {
-            if (k0 < K) b0 = *reinterpret_cast<const v8h *>(xh + (size_t)i * K + k0);
-            if (k0 + 8 < K) b1 = *reinterpret_cast<const v8h *>(xh + (size_t)i * K + k0 + 8);
-        }
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][0], b0, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][1], b1, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][0], __builtin_bit_cast(v8h, x.b[u][0]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][1], __builtin_bit_cast(v8h, x.b[u][1]), acc, 0, 0, 0);
     }
     return acc;
 }
@@ -363,48 +441,21 @@ __device__ __forceinline__ void unit_decode(const PhaseShape &S, int u, int &g, 
     n0 = (u - first) * kTileRows;
 }
 
-__device__ __forceinline__ void service_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
+// ---- the slice wavefront: its slices of A x (step 5), then SiLU of the sum of all slices
+//      (step 6) into LDS for the unit wavefront
+__device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
 {
-    const int l = threadIdx.x & 63, jl = l & 31, hf = l >> 5;
+    const int l = threadIdx.x & 63;
     bool failed = false;
-
-    // ---- which set of exchange regions this launch uses; what the previous launch used in the other
     const unsigned epoch = (unsigned)__hip_atomic_load(p.flags + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned prev_act = (unsigned)__hip_atomic_load(p.flags + 6, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned prev_mail = (unsigned)__hip_atomic_load(p.flags + 7, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
-    unsigned char *other = p.xchg + (size_t)((epoch & 1u) ^ 1u) * kStackSetBytes;
-    const rsrc_t act = make_rsrc(mine, (unsigned)kStackActBytes);
+    const unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
     const rsrc_t mail = make_rsrc(mine + kStackActBytes, (unsigned)(kStackSetBytes - kStackActBytes));
-
-    _Float16 *xh = reinterpret_cast<_Float16 *>(lds + p.xh_off);
-    _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off);
-    unsigned char *ustage = lds + p.unit_off;
-    int *tiles_all = reinterpret_cast<int *>(lds + p.tile_off);
 
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
         const StackPhase &P = p.ph[ph];
         const StackLayer *L = p.L + S.first;
-        const int par = ph & 1;
-        int *tiles = tiles_all + par * kMaxUnits * kMaxFusedM * kTileRows;
-
-        // ---- zero what the streaming side adds into during this phase
-        if (l < kMaxUnits) ctl->arrived[par][l] = 0;
-        if (l < kMaxFusedM) ctl->rowsum[par][l] = 0;
-        for (int e = l; e < S.nunits * kMaxFusedM * kTileRows; e += 64) tiles[e] = 0;
-
-        // ---- requests that do not depend on the tokens: epilogue operands of my units
-        //      (LDS-direct), weight scales, the rows of A for my slice
-        for (int i = 0; i < S.nunits; ++i) {
-            int g2, n0;
-            unit_decode(S, c + i * p.nwg, g2, n0);
-            stage_unit(p, L[g2], n0, ustage + i * p.unit_stride);
-        }
-        const unsigned swb0 = buf_load4(make_rsrc(L[0].s_w, 4u), 0u);
-        const unsigned swb1 = buf_load4(make_rsrc(S.G > 1 ? L[1].s_w : nullptr, S.G > 1 ? 4u : 0u), 0u);
-        const unsigned swb2 = buf_load4(make_rsrc(S.G > 2 ? L[2].s_w : nullptr, S.G > 2 ? 4u : 0u), 0u);
-        const unsigned swb3 = buf_load4(make_rsrc(S.G > 3 ? L[3].s_w : nullptr, S.G > 3 ? 4u : 0u), 0u);
+        _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off + (ph & 1) * p.h_par);
 
         // slices of A x of the phase: 512 columns each, at most kSplit and 64 (slice, token) rows
         const int pairs = (S.K + 63) / 64;
@@ -445,62 +496,18 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
             job_load(jr, jA, jrank, S.K, rt, kp0, kp1);
         }
 
-        // ---- the phase's tokens: from the caller's slot, or from the exchange region once
-        //      every word of it has been written; into LDS as fp16
-        {
-            const bool ext = P.x_ext != nullptr;
-            const rsrc_t xr = make_rsrc(P.x_ext, ext ? (unsigned)p.M * S.K * 2u : 0u);
-            const int pieces = p.M * S.K / 8;           // 16 bytes each
-            constexpr int kXB = 16;                     // one batch covers 8192 columns of a token
-            for (int i0 = 0; i0 < pieces; i0 += 64 * kXB) {
-                v4u v[kXB];
-                int polls = 0;
-                if (ext) {                  // (one kind of load per path: both at once would double the registers)
-#pragma unroll
-                    for (int u = 0; u < kXB; ++u) {
-                        const int i = i0 + u * 64 + l;
-                        v[u] = buf_load16(xr, (unsigned)i * 16u, i < pieces);
-                    }
-                } else {
-                    while (true) {
-                        bool ready = true;
-#pragma unroll
-                        for (int u = 0; u < kXB; ++u) {
-                            const int i = i0 + u * 64 + l;
-                            v[u] = load16_agent(act, P.src_off + (unsigned)i * 16u, i < pieces);
-                            ready = ready && !has_sentinel(v[u]);
-                        }
-                        if (failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
-                        if (++polls >= kMemPolls) {
-                            failed = true;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kXB; ++u) {
-                    const int i = i0 + u * 64 + l;
-                    if (i < pieces) *reinterpret_cast<v4u *>(xh + (size_t)i * 8) = v[u];
-                }
-            }
-        }
-        __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only: the LDS writes above have landed
-        bare_barrier();                 // A: tokens in LDS (and the zeroed counters)
-        bare_barrier();                 // B
-        // A read of the staged operands, on every path and before this phase's first store: the
-        // compiler orders it behind the LDS-direct loads (by waiting for all outstanding memory
-        // operations).  Spent here it costs a load's latency; left to the first LDS access
-        // after the stores below, it would cost their acknowledgement -- microseconds while the
-        // weight stream saturates the memory -- at the top of the next phase.
-        asm volatile("" ::"v"(*reinterpret_cast<volatile int *>(ustage)) : "memory");
-        // ---- my slices of A x (step 5) while the others quantise
+        // ---- my slices of A x (step 5): needs only the columns of the slice, so it starts as
+        //      soon as the row-blocks of the previous layer that cover them have been stored
+        const bool ext = P.x_ext != nullptr;
+        const rsrc_t xr = make_rsrc(ext ? reinterpret_cast<const unsigned char *>(P.x_ext) : mine + P.src_off,
+                                    (unsigned)p.M * S.K * 2u);
         while (job < njobs) {
             v4f acc = {0.f, 0.f, 0.f, 0.f};
-            acc = job_mfma(jr, xh, p.M, S.K, kp0, kp1, acc);
-            for (int kpb = kp0 + kUN; kpb < kp1; kpb += kUN) {
-                job_load(jr, jA, jrank, S.K, rt, kpb, kp1);
-                acc = job_mfma(jr, xh, p.M, S.K, kpb, kp1, acc);
+            JobX jx;
+            for (int kpb = kp0; kpb < kp1; kpb += kUN) {
+                if (kpb > kp0) job_load(jr, jA, jrank, S.K, rt, kpb, kp1);
+                job_xload(jx, xr, ext, p.M, S.K, kpb, kp1, failed);
+                acc = job_mfma(jr, jx, acc);
             }
             // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of the layer
             const int i = l & 15, kb = l >> 4;
@@ -512,9 +519,14 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
                 job_load(jr, jA, jrank, S.K, rt, kp0, kp1);
             }
         }
-        bare_barrier();                 // C
 
         if (S.nunits > 0) {
+            // this parity's rows were last read by the unit wavefront two phases ago
+            int spins = 0;
+            while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
+                if (++spins >= kLdsPolls) failed = true;
+                __builtin_amdgcn_s_sleep(1);
+            }
             // ---- collect every slice: h[g][m][j] = SiLU(sum_sp partial) (step 6); a lane takes four
             //      consecutive ranks of one (layer, token); one batch of loads usually covers all
             const int ge0 = rk0 > 0 ? p.M * hs0 / 4 : 0;
@@ -565,6 +577,61 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
                 }
             }
 
+        }
+        if (failed && l == 0) {
+            __hip_atomic_store(&ctl->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (l == 0) __hip_atomic_store(&ctl->h_ready, ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+}
+
+// ---- the unit wavefront: finishes the row-blocks this workgroup owns (steps 4, 7, 8) and
+//      hands their outputs on
+__device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
+{
+    const int l = threadIdx.x & 63, jl = l & 31, hf = l >> 5;
+    bool failed = false;
+
+    // ---- which set of exchange regions this launch uses; what the previous launch used in the other
+    const unsigned epoch = (unsigned)__hip_atomic_load(p.flags + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned prev_act = (unsigned)__hip_atomic_load(p.flags + 6, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned prev_mail = (unsigned)__hip_atomic_load(p.flags + 7, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
+    unsigned char *other = p.xchg + (size_t)((epoch & 1u) ^ 1u) * kStackSetBytes;
+    const rsrc_t act = make_rsrc(mine, (unsigned)kStackActBytes);
+
+    unsigned char *ustage = lds + p.unit_off;
+    int *tiles_all = reinterpret_cast<int *>(lds + p.tile_off);
+
+    for (int ph = 0; ph < p.nphases; ++ph) {
+        const PhaseShape S = shape_of(p, ph, c);
+        const StackLayer *L = p.L + S.first;
+        const int par = ph & 1;
+        int *tiles = tiles_all + par * kMaxUnits * kMaxFusedM * kTileRows;
+        const _Float16 *hs = reinterpret_cast<const _Float16 *>(lds + p.h_off + par * p.h_par);
+
+        // ---- requests that do not depend on the tokens: epilogue operands of my units
+        //      (LDS-direct) and the weight scales
+        for (int i = 0; i < S.nunits; ++i) {
+            int g2, n0;
+            unit_decode(S, c + i * p.nwg, g2, n0);
+            stage_unit(p, L[g2], n0, ustage + i * p.unit_stride);
+        }
+        const unsigned swb0 = buf_load4(make_rsrc(L[0].s_w, 4u), 0u);
+        const unsigned swb1 = buf_load4(make_rsrc(S.G > 1 ? L[1].s_w : nullptr, S.G > 1 ? 4u : 0u), 0u);
+        const unsigned swb2 = buf_load4(make_rsrc(S.G > 2 ? L[2].s_w : nullptr, S.G > 2 ? 4u : 0u), 0u);
+        const unsigned swb3 = buf_load4(make_rsrc(S.G > 3 ? L[3].s_w : nullptr, S.G > 3 ? 4u : 0u), 0u);
+        const int hs0 = h_stride(L[0].rank), hs1 = h_stride(S.G > 1 ? L[1].rank : 0),
+                  hs2 = h_stride(S.G > 2 ? L[2].rank : 0), hs3 = h_stride(S.G > 3 ? L[3].rank : 0);
+
+        if (S.nunits > 0) {
+            // ---- SiLU(A x) of the phase is in LDS once the slice wavefront says so
+            int spins = 0;
+            while (!failed && lds_load(&ctl->h_ready) < ph + 1) {
+                if (++spins >= kLdsPolls) failed = true;
+                __builtin_amdgcn_s_sleep(1);
+            }
             // ---- per unit: lane n < 32 owns output row n of the unit for every token
             for (int i = 0; i < S.nunits; ++i) {
                 const unsigned char *op = ustage + i * p.unit_stride;
@@ -581,6 +648,22 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
                     }
                     __builtin_amdgcn_s_sleep(1);
                 }
+                if (lds_load(&ctl->failed) != 0) failed = true;
+                // the unit's sums, then this parity's words are ready for the phase after next
+                int a[kMaxFusedM], rs[kMaxFusedM];
+                float sxv[kMaxFusedM];
+#pragma unroll
+                for (int m = 0; m < kMaxFusedM; ++m) {
+                    a[m] = tiles[(i * kMaxFusedM + m) * kTileRows + jl];
+                    rs[m] = 0;
+#pragma unroll
+                    for (int ww = 0; ww < kStream; ++ww) rs[m] += ctl->rowsum_part[par][ww][m];
+                    sxv[m] = ctl->sx[par][m];
+                }
+#pragma unroll
+                for (int m = 0; m < kMaxFusedM; ++m)
+                    if (l < 32) tiles[(i * kMaxFusedM + m) * kTileRows + l] = 0;
+                if (l == 0) ctl->arrived[par][i] = 0;
                 v16f corr = (v16f){};
                 float gate = 0.f;
                 if (Lg.rank > 0) {
@@ -599,8 +682,7 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
 #pragma unroll
                 for (int m = 0; m < kMaxFusedM; ++m) {
                     if (m < p.M) {
-                        const int a = tiles[(i * kMaxFusedM + m) * kTileRows + jl] - ctl->rowsum[par][m];
-                        _Float16 o = (_Float16)((float)a * (ctl->sx[par][m] * s_w) + gate * corr[m]);
+                        _Float16 o = (_Float16)((float)(a[m] - rs[m]) * (sxv[m] * s_w) + gate * corr[m]);
                         if (o != o || failed) o = __builtin_bit_cast(_Float16, (unsigned short)0x7e00);
                         if (l < 32 && n < Lg.N) Lg.y[(size_t)m * Lg.N + n] = o;
                         // exchange copy: 32 lanes x 2 bytes gathered into 16 lanes x 4 bytes, padding
@@ -615,6 +697,8 @@ __device__ __forceinline__ void service_wave(const StackParams &p, unsigned char
                 }
             }
         }
+        // the other wavefronts may now reuse this parity's words (two phases from here)
+        if (l == 0) __hip_atomic_store(&ctl->svc_done, ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 
         // ---- my share of the sentinels for the launch after this one (once, in the first phase)
         if (ph == 0) {
@@ -652,7 +736,14 @@ __global__ __launch_bounds__(512) void stack_kernel(const StackParams p)
     __shared__ Control ctl;
     const int c = blockIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (w == kStream) service_wave(p, lds, &ctl, c);
+    // everything the two sides add into or count with starts at zero; afterwards the service
+    // wavefront resets what it has consumed
+    int *tiles = reinterpret_cast<int *>(lds + p.tile_off);
+    for (int e = threadIdx.x; e < 2 * kMaxUnits * kMaxFusedM * kTileRows; e += 512) tiles[e] = 0;
+    for (int e = threadIdx.x; e < (int)(sizeof(Control) / sizeof(int)); e += 512) reinterpret_cast<int *>(&ctl)[e] = 0;
+    __syncthreads();
+    if (w == kStream) slice_wave(p, lds, &ctl, c);
+    else if (w == kStream + 1) unit_wave(p, lds, &ctl, c);
     else streaming_wave(p, lds, &ctl, c);
 }
 
@@ -716,12 +807,11 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
     const int kp = round_up(kmax, kTileCols);
     p.xstride = kp + 16;
     size_t off = ((size_t)M * p.xstride + 15) & ~size_t(15);     // quantised tokens at offset 0
-    p.xh_off = (int)off;
-    off += ((size_t)M * kmax * 2 + 15) & ~size_t(15);
     p.tile_off = (int)off;
     off += (size_t)2 * kMaxUnits * kMaxFusedM * kTileRows * sizeof(int);
-    p.h_off = (int)off;
-    off += (size_t)gmax * M * kHsStride * sizeof(_Float16);
+    p.h_off = (int)off;                                           // one set of rows per phase parity
+    p.h_par = (int)((size_t)gmax * M * kHsStride * sizeof(_Float16));
+    off += (size_t)2 * p.h_par;
     off = (off + 1023) & ~size_t(1023);
     p.unit_off = (int)off;
     p.unit_alpha = 64 * hstride_max;
