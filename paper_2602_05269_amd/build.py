@@ -14,6 +14,10 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fhip-fp32-correctly-rounded-divide-sqrt", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the whole-stack kernel indexes its by-value arguments at run-time offsets from many unrolled
+    # places; above the default limit of 300 uses the compiler copies all 4 KiB of them into
+    # private memory per thread instead of reading the argument segment
+    "-mllvm", "-instcombine-max-copied-from-constant-users=4000",
     "-Wall", "-Wno-unused-function",
 ]
 

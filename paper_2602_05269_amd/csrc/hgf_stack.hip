@@ -27,6 +27,8 @@
 // is set in the workspace, the affected outputs are NaN and later waits are skipped.
 #include "hgf_internal.h"
 
+#include <type_traits>
+
 namespace hgf {
 
 namespace {
@@ -212,7 +214,7 @@ __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned ch
     unsigned by0 = 0, by1 = 0, by2 = 0, by3 = 0;
     const void *lbase = nullptr;
     unsigned lbytes = 0, lrow = 0;
-    auto load_unit = [&]() {            // the load cursor has entered unit li of phase lp
+    auto load_unit = [&]() __attribute__((always_inline)) {            // the load cursor has entered unit li of phase lp
         const bool valid = lp < p.nphases && li < LS.nunits;
         const int u = valid ? c + li * p.nwg : 0;
         int first = 0;
@@ -224,7 +226,7 @@ __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned ch
         if (!valid) lbytes = 0;         // padding steps and steps past the last phase read zeros
         lrow = (unsigned)(u - first) * LS.KT;
     };
-    auto load_phase = [&]() {           // the load cursor has entered phase lp
+    auto load_phase = [&]() __attribute__((always_inline)) {           // the load cursor has entered phase lp
         if (lp < p.nphases) {
             LS = shape_of(p, lp, c);
             const StackLayer *L = p.L + LS.first;
@@ -247,7 +249,7 @@ __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned ch
     };
     load_phase();
     v4u wq[kPF];
-    auto issue = [&](v4u &dst) {
+    auto issue = [&](v4u &dst) __attribute__((always_inline)) {
         const int kt = lj * kStream + w;
         const rsrc_t wr = make_rsrc(lbase, lbytes);
         dst = buf_load16_stream(wr, kt < LS.KT ? (lrow + kt) * kTileBytes + l * 16 : kOob);
@@ -295,7 +297,7 @@ __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned ch
         int *tiles = reinterpret_cast<int *>(lds + p.tile_off) + par * kMaxUnits * kMaxFusedM * kTileRows;
         const int steps = ring_steps(S);
         const unsigned char *xlane = lds + (jl < p.M ? jl : 0) * p.xstride + hf * 16;
-        auto xload = [&](v4i (&dst)[4], int j) {
+        auto xload = [&](v4i (&dst)[4], int j) __attribute__((always_inline)) {
             int kt = j * kStream + w;
             kt = kt < S.KT ? kt : S.KT - 1;
 #pragma unroll
@@ -354,24 +356,29 @@ __device__ __forceinline__ void job_load(JobRegs &r, const _Float16 *A, int rank
         r.a[u][1] = buf_load8h<true>(ar, (unsigned)j * K + k0 + 8, K - k0 - 8, ok);
     }
 }
-// The tokens' side of the same batch: lane (i, kb) holds token i's 16 columns at 64*kp + 16*kb,
-// read from the caller's slot or, once no word is the sentinel, from the exchange region.
+// The tokens' side of the same batch: 512 columns per token, one 16-byte piece per lane, read
+// from the caller's slot or, once no word is the sentinel, from the exchange region (one
+// request per token and try, so that a try costs little more than the memory's latency).
+// The pieces then pass through 1 KiB of LDS per token into the operand layout: lane (i, kb)
+// holds token i's 16 columns at 64*kp + 16*kb.
 struct JobX {
     v4u b[kUN][2];
 };
-__device__ __forceinline__ void job_xload(JobX &x, rsrc_t xr, bool ext, int M, int K, int kpb, int kp1, bool &failed)
+template <int MT>
+__device__ __forceinline__ void job_xfetch(JobX &x, unsigned char *jxl, rsrc_t xr, bool ext, int M, int K, int kpb,
+                                           int kp1, bool &failed)
 {
     const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
+    const int col = kpb * 64 + l * 8;
+    const bool mine = kpb + (l >> 3) < kp1 && col < K;
+    v4u v[MT];
     int polls = 0;
     while (true) {
         bool ready = true;
 #pragma unroll
-        for (int u = 0; u < kUN; ++u) {
-            const int k0 = (kpb + u) * 64 + kb * 16;
-            const bool ok = i < M && (kpb + u) < kp1;
-            x.b[u][0] = load16_agent(xr, (unsigned)(i * K + k0) * 2u, ok && k0 < K);
-            x.b[u][1] = load16_agent(xr, (unsigned)(i * K + k0 + 8) * 2u, ok && k0 + 8 < K);
-            ready = ready && !has_sentinel(x.b[u][0]) && !has_sentinel(x.b[u][1]);
+        for (int m = 0; m < MT; ++m) {
+            v[m] = load16_agent(xr, (unsigned)(m * K + col) * 2u, mine && m < M);
+            ready = ready && !has_sentinel(v[m]);
         }
         if (ext || failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
         if (++polls >= kMemPolls) {
@@ -379,6 +386,14 @@ __device__ __forceinline__ void job_xload(JobX &x, rsrc_t xr, bool ext, int M, i
             break;
         }
         __builtin_amdgcn_s_sleep(1);
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) *reinterpret_cast<v4u *>(jxl + m * 1024 + l * 16) = v[m];
+    const v4u zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < kUN; ++u) {
+        x.b[u][0] = i < M ? *reinterpret_cast<const v4u *>(jxl + i * 1024 + u * 128 + kb * 32) : zero;
+        x.b[u][1] = i < M ? *reinterpret_cast<const v4u *>(jxl + i * 1024 + u * 128 + kb * 32 + 16) : zero;
     }
 }
 __device__ __forceinline__ v4f job_mfma(const JobRegs &r, const JobX &x, v4f acc)
@@ -450,51 +465,73 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
     const unsigned epoch = (unsigned)__hip_atomic_load(p.flags + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
     const rsrc_t mail = make_rsrc(mine + kStackActBytes, (unsigned)(kStackSetBytes - kStackActBytes));
+    unsigned char *jxl = lds + p.jx_off;
+
+    // ---- the phase's slices of A x and the one this workgroup starts with.  The rows of A for
+    //      it are requested a phase ahead, right after the previous phase's SiLU(A x): they come
+    //      from HBM through queues the weight stream keeps full, and loads return in order, so
+    //      requested just before the tokens they would hold the tokens back by microseconds.
+    int pairs = 0, pps = 0, Sn = 0, rk0 = 0, rk1 = 0, rk2 = 0, rk3 = 0, hs0 = 32, hs1 = 32, hs2 = 32, hs3 = 32;
+    int jb1 = 0, jb2 = 0, jb3 = 0, njobs = 0, jK = 0;
+    unsigned mo0 = 0, mo1 = 0, mo2 = 0, mo3 = 0;
+    int jfirst = 0;                     // (an index, not a pointer into the arguments: a pointer carried
+    int job = 0;                        //  from phase to phase makes the compiler copy them to private memory)
+    JobRegs jr;
+    int g = 0, rt = 0, sp = 0, kp0 = 0, kp1 = 0, jrank = 0, jhs = 0;
+    unsigned jmo = 0;
+    const _Float16 *jA = nullptr;
+    auto job_decode = [&]() __attribute__((always_inline)) {
+        g = 0;
+        int first = 0;
+        jrank = rk0; jhs = hs0; jmo = mo0;
+        if (job >= jb1) { g = 1; first = jb1; jrank = rk1; jhs = hs1; jmo = mo1; }
+        if (job >= jb2) { g = 2; first = jb2; jrank = rk2; jhs = hs2; jmo = mo2; }
+        if (job >= jb3) { g = 3; first = jb3; jrank = rk3; jhs = hs3; jmo = mo3; }
+        jA = p.L[jfirst + g].A;
+        rt = (job - first) / Sn;
+        sp = (job - first) % Sn;
+        kp0 = sp * pps;
+        kp1 = min(kp0 + pps, pairs);
+    };
+    auto plan_phase = [&](int ph) __attribute__((always_inline)) {
+        const StackPhase &P = p.ph[ph];
+        jfirst = P.first_layer;
+        const StackLayer *JL = p.L + jfirst;
+        jK = P.K;
+        // slices of 512 columns each, at most kSplit and 64 (slice, token) rows
+        pairs = (jK + 63) / 64;
+        int nsl = (pairs + 7) / 8;
+        if (nsl > kSplit) nsl = kSplit;
+        if (nsl > 64 / p.M) nsl = 64 / p.M;
+        pps = (pairs + nsl - 1) / nsl;
+        Sn = (pairs + pps - 1) / pps;
+        rk0 = JL[0].rank;
+        rk1 = P.G > 1 ? JL[1].rank : 0;
+        rk2 = P.G > 2 ? JL[2].rank : 0;
+        rk3 = P.G > 3 ? JL[3].rank : 0;
+        hs0 = h_stride(rk0);
+        hs1 = h_stride(rk1);
+        hs2 = h_stride(rk2);
+        hs3 = h_stride(rk3);
+        jb1 = (rk0 + 15) / 16 * Sn;
+        jb2 = jb1 + (rk1 + 15) / 16 * Sn;
+        jb3 = jb2 + (rk2 + 15) / 16 * Sn;
+        njobs = jb3 + (rk3 + 15) / 16 * Sn;
+        // byte offsets of the layers' partial sums inside the phase's region: [slice][token][hstride] fp32
+        mo0 = P.mail_off;
+        mo1 = mo0 + (unsigned)(rk0 > 0 ? Sn * p.M * hs0 * 4 : 0);
+        mo2 = mo1 + (unsigned)(rk1 > 0 ? Sn * p.M * hs1 * 4 : 0);
+        mo3 = mo2 + (unsigned)(rk2 > 0 ? Sn * p.M * hs2 * 4 : 0);
+        job = p.nwg - 1 - c;            // the highest workgroups, which own the fewest units, come first
+        job_decode();                   // (without a branch: no job, no columns, and every request is void)
+        job_load(jr, jA, jrank, jK, rt, kp0, job < njobs ? kp1 : kp0);
+    };
+    plan_phase(0);
 
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
         const StackPhase &P = p.ph[ph];
-        const StackLayer *L = p.L + S.first;
         _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off + (ph & 1) * p.h_par);
-
-        // slices of A x of the phase: 512 columns each, at most kSplit and 64 (slice, token) rows
-        const int pairs = (S.K + 63) / 64;
-        int nsl = (pairs + 7) / 8;
-        if (nsl > kSplit) nsl = kSplit;
-        if (nsl > 64 / p.M) nsl = 64 / p.M;
-        const int pps = (pairs + nsl - 1) / nsl;
-        const int Sn = (pairs + pps - 1) / pps;
-        const int rk0 = L[0].rank, rk1 = S.G > 1 ? L[1].rank : 0, rk2 = S.G > 2 ? L[2].rank : 0,
-                  rk3 = S.G > 3 ? L[3].rank : 0;
-        const int hs0 = h_stride(rk0), hs1 = h_stride(rk1), hs2 = h_stride(rk2), hs3 = h_stride(rk3);
-        const int jb1 = (rk0 + 15) / 16 * Sn, jb2 = jb1 + (rk1 + 15) / 16 * Sn, jb3 = jb2 + (rk2 + 15) / 16 * Sn,
-                  njobs = jb3 + (rk3 + 15) / 16 * Sn;
-        // byte offsets of the layers' partial sums inside the phase's region: [slice][token][hstride] fp32
-        const unsigned mo0 = P.mail_off, mo1 = mo0 + (unsigned)(rk0 > 0 ? Sn * p.M * hs0 * 4 : 0),
-                       mo2 = mo1 + (unsigned)(rk1 > 0 ? Sn * p.M * hs1 * 4 : 0),
-                       mo3 = mo2 + (unsigned)(rk2 > 0 ? Sn * p.M * hs2 * 4 : 0);
-        int job = p.nwg - 1 - c;        // the highest workgroups, which own the fewest units, come first
-        JobRegs jr;
-        int g = 0, rt = 0, sp = 0, kp0 = 0, kp1 = 0, jrank = 0, jhs = 0;
-        unsigned jmo = 0;
-        const _Float16 *jA = nullptr;
-        auto job_decode = [&]() {
-            g = 0;
-            int first = 0;
-            jrank = rk0; jhs = hs0; jmo = mo0;
-            if (job >= jb1) { g = 1; first = jb1; jrank = rk1; jhs = hs1; jmo = mo1; }
-            if (job >= jb2) { g = 2; first = jb2; jrank = rk2; jhs = hs2; jmo = mo2; }
-            if (job >= jb3) { g = 3; first = jb3; jrank = rk3; jhs = hs3; jmo = mo3; }
-            jA = L[g].A;
-            rt = (job - first) / Sn;
-            sp = (job - first) % Sn;
-            kp0 = sp * pps;
-            kp1 = min(kp0 + pps, pairs);
-        };
-        if (job < njobs) {
-            job_decode();
-            job_load(jr, jA, jrank, S.K, rt, kp0, kp1);
-        }
 
         // ---- my slices of A x (step 5): needs only the columns of the slice, so it starts as
         //      soon as the row-blocks of the previous layer that cover them have been stored
@@ -506,7 +543,9 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             JobX jx;
             for (int kpb = kp0; kpb < kp1; kpb += kUN) {
                 if (kpb > kp0) job_load(jr, jA, jrank, S.K, rt, kpb, kp1);
-                job_xload(jx, xr, ext, p.M, S.K, kpb, kp1, failed);
+                if (p.M == 1) job_xfetch<1>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, failed);
+                else if (p.M == 2) job_xfetch<2>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, failed);
+                else job_xfetch<4>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, failed);
                 acc = job_mfma(jr, jx, acc);
             }
             // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of the layer
@@ -549,26 +588,34 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                 const bool wanted = inside && j < (rank + 15) / 16 * 16;
                 const unsigned at = mo + (unsigned)idx * 16u;
                 const unsigned step = (unsigned)p.M * hstride * 4u;
-                v4f part[kSplit];
-                int polls = 0;
-                while (true) {
-                    bool ready = true;
+                v4f h = {0.f, 0.f, 0.f, 0.f};
+                // all slices of the lane's four sums are requested at once; two sizes of that batch,
+                // because a try costs as many requests and comparisons as the batch is long
+                auto gather = [&](auto ns) __attribute__((always_inline)) {
+                    constexpr int NS = decltype(ns)::value;
+                    v4f part[NS];
+                    int polls = 0;
+                    while (true) {
+                        bool ready = true;
 #pragma unroll
-                    for (int sl = 0; sl < kSplit; ++sl) {
-                        const v4u raw = load16_agent(mail, at + (unsigned)sl * step, wanted && sl < Sn);
-                        ready = ready && !has_sentinel(raw);
-                        part[sl] = __builtin_bit_cast(v4f, raw);
+                        for (int sl = 0; sl < NS; ++sl) {
+                            const v4u raw = load16_agent(mail, at + (unsigned)sl * step, wanted && sl < Sn);
+                            ready = ready && !has_sentinel(raw);
+                            part[sl] = __builtin_bit_cast(v4f, raw);
+                        }
+                        if (failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
+                        if (++polls >= kMemPolls) {
+                            failed = true;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
                     }
-                    if (failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
-                    if (++polls >= kMemPolls) {
-                        failed = true;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(1);
-                }
-                v4f h = part[0];
+                    h = part[0];
 #pragma unroll
-                for (int sl = 1; sl < kSplit; ++sl) h += part[sl];          // slice order: deterministic
+                    for (int sl = 1; sl < NS; ++sl) h += part[sl];          // slice order: deterministic
+                };
+                if (Sn <= 8) gather(std::integral_constant<int, 8>{});
+                else gather(std::integral_constant<int, kSplit>{});
                 if (inside) {
                     v4h o;
 #pragma unroll
@@ -583,6 +630,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (l == 0) __hip_atomic_store(&ctl->h_ready, ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (ph + 1 < p.nphases) plan_phase(ph + 1);
     }
 }
 
@@ -633,6 +681,8 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 __builtin_amdgcn_s_sleep(1);
             }
             // ---- per unit: lane n < 32 owns output row n of the unit for every token
+            int rs[kMaxFusedM] = {0, 0, 0, 0};
+            float sxv[kMaxFusedM] = {0.f, 0.f, 0.f, 0.f};
             for (int i = 0; i < S.nunits; ++i) {
                 const unsigned char *op = ustage + i * p.unit_stride;
                 int gg, n0;
@@ -650,15 +700,17 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 }
                 if (lds_load(&ctl->failed) != 0) failed = true;
                 // the unit's sums, then this parity's words are ready for the phase after next
-                int a[kMaxFusedM], rs[kMaxFusedM];
-                float sxv[kMaxFusedM];
+                int a[kMaxFusedM];
 #pragma unroll
-                for (int m = 0; m < kMaxFusedM; ++m) {
-                    a[m] = tiles[(i * kMaxFusedM + m) * kTileRows + jl];
-                    rs[m] = 0;
+                for (int m = 0; m < kMaxFusedM; ++m) a[m] = tiles[(i * kMaxFusedM + m) * kTileRows + jl];
+                if (i == 0) {           // every streaming wavefront has posted: so are the tokens' sums and scales
 #pragma unroll
-                    for (int ww = 0; ww < kStream; ++ww) rs[m] += ctl->rowsum_part[par][ww][m];
-                    sxv[m] = ctl->sx[par][m];
+                    for (int m = 0; m < kMaxFusedM; ++m) {
+                        rs[m] = 0;
+#pragma unroll
+                        for (int ww = 0; ww < kStream; ++ww) rs[m] += ctl->rowsum_part[par][ww][m];
+                        sxv[m] = ctl->sx[par][m];
+                    }
                 }
 #pragma unroll
                 for (int m = 0; m < kMaxFusedM; ++m)
@@ -813,6 +865,8 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
     p.h_par = (int)((size_t)gmax * M * kHsStride * sizeof(_Float16));
     off += (size_t)2 * p.h_par;
     off = (off + 1023) & ~size_t(1023);
+    p.jx_off = (int)off;                                          // the slice wavefront's pieces of the tokens
+    off += (size_t)kMaxFusedM * 1024;
     p.unit_off = (int)off;
     p.unit_alpha = 64 * hstride_max;
     p.unit_stride = p.unit_alpha + 256;
