@@ -243,7 +243,7 @@ struct StackParams {
     int32_t *flags;               // [2] sticky error, [4] launch counter, [5] workgroups done, [6], [7] extents used
     unsigned char *xchg;          // two sets of kStackSetBytes
     unsigned act_used, mail_used;
-    int xstride, h_par, tile_off, h_off, unit_off, unit_stride, unit_alpha, jx_off;   // LDS layout
+    int xstride, h_par, tile_off, h_off, unit_off, unit_stride, unit_alpha, jx_off, ring_off, ring_slots;   // LDS layout
     StackPhase ph[kStackMaxPhases];
     StackLayer L[kStackMaxLayers];
 };

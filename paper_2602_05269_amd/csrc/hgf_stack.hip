@@ -27,17 +27,24 @@
 // is set in the workspace, the affected outputs are NaN and later waits are skipped.
 #include "hgf_internal.h"
 
+
 #include <type_traits>
 
 namespace hgf {
 
 namespace {
 
-constexpr int kStream = 6;             // streaming wavefronts per workgroup (wavefronts 6 and 7 serve them)
-#ifndef HGF_STACK_PF
-#define HGF_STACK_PF 8
+constexpr int kStream = 8;             // contracting wavefronts per workgroup (0..7): two per SIMD, so that one's
+                                       // MFMAs overlap the other's unpacking of the 2-bit codes
+constexpr int kLoaders = 2;            // loader wavefronts (8, 9): each feeds four contracting ones; 10, 11 serve
+constexpr int kFeed = kStream / kLoaders;
+constexpr int kWaves = kStream + kLoaders + 2;
+#ifndef HGF_STACK_WINDOW
+#define HGF_STACK_WINDOW 6
 #endif
-constexpr int kPF = HGF_STACK_PF;      // weight tiles in flight per streaming wavefront
+constexpr int kWindow = HGF_STACK_WINDOW;   // groups of kFeed weight tiles a loader keeps in flight
+constexpr int kMinRing = kWindow + 4;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow)
+constexpr int kMaxRing = 48;
 constexpr int kMaxUnits = 16;          // units per workgroup and phase at most
 constexpr int kLdsPolls = 1 << 22;     // bound of a wait on LDS (about a second)
 constexpr int kMemPolls = 1 << 18;     // bound of a wait on an exchange region (about a second)
@@ -58,6 +65,8 @@ struct Control {                       // LDS words shared by the two sides; [2]
     int svc_done;                      // phases whose units the unit wavefront has finished
     int h_ready;                       // phases whose SiLU(A x) the slice wavefront has put into LDS
     int failed;                        // a wait of the streaming side has expired
+    int ready[kStream];                // weight tiles of the wavefront's ring that have landed in LDS, in all
+    int consumed[kStream];             // ... and how many of them it has read
 };
 
 __device__ __forceinline__ int lds_load(const int *p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
@@ -103,20 +112,12 @@ __device__ __forceinline__ PhaseShape shape_of(const StackParams &p, int ph, int
     s.nunits = c < s.units ? (s.units - c + p.nwg - 1) / p.nwg : 0;
     return s;
 }
-// steps of a streaming wavefront's ring in a phase: its tiles, padded to whole turns of the ring
-// (at least one turn, so that the cursor never has to loop over empty phases)
-__device__ __forceinline__ int ring_steps(const PhaseShape &s)
-{
-    const int n = (s.nunits * s.TPW + kPF - 1) / kPF * kPF;
-    return n > 0 ? n : kPF;
-}
-
 // ------------------------------------------------------------------ streaming side
 // Per-token absmax int8 quantisation (Sec. 2.2.1) of the columns wavefront w contracts: the
-// k-tiles w, w+7, ... (128 columns each).  The columns come from the caller's slot or, once
+// k-tiles w, w+8, ... (128 columns each).  The columns come from the caller's slot or, once
 // no word of them is the sentinel, from the exchange region; they stay in registers between
-// the two passes.  The seven wavefronts exchange their absmax parts through LDS and a counter
-// (`sync_target`: its value once all seven have posted this phase's part); the quantised
+// the two passes.  The eight wavefronts exchange their absmax parts through LDS and a counter
+// (`sync_target`: its value once all eight have posted this phase's part); the quantised
 // columns go to the token rows in LDS, where only this wavefront reads them.
 template <int MT>
 __device__ __forceinline__ void fetch_quantise(const StackParams &p, const PhaseShape &S, rsrc_t xr, bool ext,
@@ -124,10 +125,11 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
                                                bool &failed)
 {
     const int l = threadIdx.x & 63, par = ph & 1;
-    constexpr int XU = 4;               // 64 lanes x 4 pieces of 8 columns >= 14 tiles of a token
+    constexpr int XU = 3;               // 64 lanes x 3 pieces of 8 columns = 12 tiles of a token
     const int pc = l & 15;
     v4u v[MT][XU];
     int polls = 0;
+#pragma clang loop unroll(disable)
     while (true) {
         bool ready = true;
 #pragma unroll
@@ -161,11 +163,13 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     }
     if (l == 0) __hip_atomic_fetch_add(&ctl->sync, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     polls = 0;
+#pragma clang loop unroll(disable)
     while (!failed && lds_load(&ctl->sync) < sync_target) {
         if (++polls >= kLdsPolls) failed = true;
     }
     // what this phase shares with the service side was last used two phases ago
     polls = 0;
+#pragma clang loop unroll(disable)
     while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
         if (++polls >= kLdsPolls) failed = true;
         __builtin_amdgcn_s_sleep(1);
@@ -201,80 +205,114 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     }
 }
 
-__device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
+// LDS accesses the compiler must not see: around LDS-direct loads it orders every LDS access it
+// knows of behind all outstanding memory operations, which would empty the loader's window.
+__device__ __forceinline__ unsigned lds_offset(const void *q)
+{
+    return (unsigned)reinterpret_cast<size_t>((__attribute__((address_space(3))) const void *)q);
+}
+__device__ __forceinline__ int lds_peek(unsigned at)
+{
+    int v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(at) : "memory");
+    return v;
+}
+__device__ __forceinline__ void lds_poke(unsigned at, int v)
+{
+    asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(at), "v"(v) : "memory");
+}
+
+// ---- a loader wavefront: streams the weight tiles of kFeed contracting wavefronts (a = kFeed*ld
+//      and the following) into their rings in LDS with LDS-direct loads, in the order those will
+//      read them: phase by phase, row-block by row-block, k-turn by k-turn.  Weights do not
+//      depend on activations, so it runs ahead of the phases as far as the rings reach; it keeps
+//      kWindow groups of requests in flight (enough to cover the memory's latency, few enough
+//      that the queues stay short for the other wavefronts' exchanges) and publishes a group once
+//      kWindow younger ones have been issued and the wait count says it has landed.
+__device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c, int ld)
+{
+    const int l = threadIdx.x & 63;
+    const int a = kFeed * ld;
+    unsigned char *ring = lds + p.ring_off + (size_t)a * p.ring_slots * kTileBytes;
+    const unsigned ready_at = lds_offset(&ctl->ready[a]), cons_at = lds_offset(&ctl->consumed[a]);
+    const unsigned failed_at = lds_offset(&ctl->failed);
+    auto publish = [&](int n) __attribute__((always_inline)) {
+#pragma unroll
+        for (int f = 0; f < kFeed; ++f) lds_poke(ready_at + 4u * f, n);
+    };
+    int n = 0, slot = 0, freed = 0;     // groups issued; ring slot of the next; groups all readers are known to have read
+    bool failed = false;
+    for (int ph = 0; ph < p.nphases; ++ph) {
+        const PhaseShape S = shape_of(p, ph, c);
+        const StackLayer *L = p.L + S.first;
+        for (int i = 0; i < S.nunits; ++i) {
+            const int u = c + i * p.nwg;
+            int g = 0, first = 0;
+            if (u >= S.us1) { g = 1; first = S.us1; }
+            if (u >= S.us2) { g = 2; first = S.us2; }
+            if (u >= S.us3) { g = 3; first = S.us3; }
+            const unsigned rows = (unsigned)((L[g].N + kTileRows - 1) / kTileRows);
+            const rsrc_t wr = make_rsrc(L[g].packed, rows * S.KT * kTileBytes);
+            const unsigned row = (unsigned)(u - first) * S.KT;
+            for (int j = 0; j < S.TPW; ++j) {
+                // room in the rings?  While there is none nothing is gained by keeping the
+                // window open: let everything land, publish it, and wait for the readers.
+                if (n - freed >= p.ring_slots) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    publish(n);
+                    int spins = 0;
+#pragma clang loop unroll(disable)
+                    while (!failed) {
+                        freed = lds_peek(cons_at);
+#pragma unroll
+                        for (int f = 1; f < kFeed; ++f) freed = min(freed, lds_peek(cons_at + 4u * f));
+                        if (n - freed < p.ring_slots) break;
+                        if (++spins >= kLdsPolls || lds_peek(failed_at) != 0) failed = true;
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                }
+#pragma unroll
+                for (int f = 0; f < kFeed; ++f) {
+                    const int kt = j * kStream + a + f;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        wr, (lds_ptr_t)(ring + ((size_t)f * p.ring_slots + slot) * kTileBytes), 16,
+                        (int)(kt < S.KT ? (row + kt) * kTileBytes + l * 16 : kOob), 0, 0, 2);
+                }
+                ++n;
+                slot = slot + 1 == p.ring_slots ? 0 : slot + 1;
+                if (n > kWindow) {
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * kWindow) : "memory");
+                    publish(n - kWindow);
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    publish(n);
+    if (failed && l == 0) {
+        lds_poke(failed_at, 1);
+        __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ---- a contracting wavefront: quantises its columns of the phase's tokens, then contracts the
+//      k-tiles w, w+8, ... of every row-block of the workgroup with them (Alg. 1 steps 2-3),
+//      reading the tiles from its ring in LDS as the loader publishes them
+__device__ __forceinline__ void contract_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
 {
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int jl = l & 31, hf = l >> 5;
-
-    // ---- load cursor: phase lp, step ls of its padded ring sequence (unit li, tile lj)
-    int lp = 0, ls = 0, li = 0, lj = 0, lsteps = 0;
-    PhaseShape LS;
-    const void *pk0 = nullptr, *pk1 = nullptr, *pk2 = nullptr, *pk3 = nullptr;
-    unsigned by0 = 0, by1 = 0, by2 = 0, by3 = 0;
-    const void *lbase = nullptr;
-    unsigned lbytes = 0, lrow = 0;
-    auto load_unit = [&]() __attribute__((always_inline)) {            // the load cursor has entered unit li of phase lp
-        const bool valid = lp < p.nphases && li < LS.nunits;
-        const int u = valid ? c + li * p.nwg : 0;
-        int first = 0;
-        lbase = pk0;
-        lbytes = by0;
-        if (u >= LS.us1) { lbase = pk1; lbytes = by1; first = LS.us1; }
-        if (u >= LS.us2) { lbase = pk2; lbytes = by2; first = LS.us2; }
-        if (u >= LS.us3) { lbase = pk3; lbytes = by3; first = LS.us3; }
-        if (!valid) lbytes = 0;         // padding steps and steps past the last phase read zeros
-        lrow = (unsigned)(u - first) * LS.KT;
-    };
-    auto load_phase = [&]() __attribute__((always_inline)) {           // the load cursor has entered phase lp
-        if (lp < p.nphases) {
-            LS = shape_of(p, lp, c);
-            const StackLayer *L = p.L + LS.first;
-            pk0 = L[0].packed;
-            by0 = (unsigned)((L[0].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes;
-            pk1 = LS.G > 1 ? L[1].packed : nullptr;
-            by1 = LS.G > 1 ? (unsigned)((L[1].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes : 0u;
-            pk2 = LS.G > 2 ? L[2].packed : nullptr;
-            by2 = LS.G > 2 ? (unsigned)((L[2].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes : 0u;
-            pk3 = LS.G > 3 ? L[3].packed : nullptr;
-            by3 = LS.G > 3 ? (unsigned)((L[3].N + kTileRows - 1) / kTileRows) * LS.KT * kTileBytes : 0u;
-            lsteps = ring_steps(LS);
-        } else {
-            lsteps = 0x7fffffff;        // past the end: zeros for ever
-        }
-        ls = 0;
-        li = 0;
-        lj = 0;
-        load_unit();
-    };
-    load_phase();
-    v4u wq[kPF];
-    auto issue = [&](v4u &dst) __attribute__((always_inline)) {
-        const int kt = lj * kStream + w;
-        const rsrc_t wr = make_rsrc(lbase, lbytes);
-        dst = buf_load16_stream(wr, kt < LS.KT ? (lrow + kt) * kTileBytes + l * 16 : kOob);
-        ++ls;
-        if (++lj == LS.TPW) {
-            lj = 0;
-            ++li;
-            load_unit();
-        }
-        if (ls == lsteps) {
-            ++lp;
-            load_phase();
-        }
-    };
-#pragma unroll
-    for (int t = 0; t < kPF; ++t) issue(wq[t]);
 
     const unsigned epoch = (unsigned)__hip_atomic_load(p.flags + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const unsigned char *mine = p.xchg + (size_t)(epoch & 1u) * kStackSetBytes;
     bool failed = false;
     int sync_target = 0;
+    int gs = 0, slot = 0, known = 0;    // tiles read so far; ring slot of the next; tiles known to have landed
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
         const int par = ph & 1;
-        if (S.nunits > 0) {
+        if (S.nunits == 0) continue;
+        {
             const StackPhase &P = p.ph[ph];
             const bool ext = P.x_ext != nullptr;
             const rsrc_t xr = make_rsrc(ext ? reinterpret_cast<const unsigned char *>(P.x_ext) : mine + P.src_off,
@@ -285,55 +323,119 @@ __device__ __forceinline__ void streaming_wave(const StackParams &p, unsigned ch
             if (p.M == 1) fetch_quantise<1>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
             else if (p.M == 2) fetch_quantise<2>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
             else fetch_quantise<4>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
-            if (failed && !was && l == 0) __hip_atomic_store(&ctl->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-
-        // ---- contraction: one ring slot per step.  Straight-line code: the refill of a slot is
-        //      unconditional and the loop has no inner loop (either would cost the ring its
-        //      precise wait counts), and so are the MFMAs: a slot past the row-block's last
-        //      tile holds zeros, which add nothing.  The tokens are the matrix rows, so lanes
-        //      without a token simply read token 0: their rows of the result are never used.
-        //      The token operands of the next step are read from LDS while this step computes.
-        int *tiles = reinterpret_cast<int *>(lds + p.tile_off) + par * kMaxUnits * kMaxFusedM * kTileRows;
-        const int steps = ring_steps(S);
-        const unsigned char *xlane = lds + (jl < p.M ? jl : 0) * p.xstride + hf * 16;
-        auto xload = [&](v4i (&dst)[4], int j) __attribute__((always_inline)) {
-            int kt = j * kStream + w;
-            kt = kt < S.KT ? kt : S.KT - 1;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) dst[q] = *reinterpret_cast<const v4i *>(xlane + kt * kTileCols + q * 32);
-        };
-        int ci = 0, cj = 0;
-        v16i acc = (v16i){};
-        v4i xv[2][4];
-        xload(xv[0], 0);
-        for (int s0 = 0; s0 < steps; s0 += kPF) {
-#pragma unroll
-            for (int t = 0; t < kPF; ++t) {
-                const int nj = cj + 1 == S.TPW ? 0 : cj + 1;
-                xload(xv[(t + 1) & 1], nj);
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(xv[t & 1][q], widen_codes(wq[t][q]), acc, 0, 0, 0);
-                issue(wq[t]);
-                cj = nj;
-                if (nj == 0) {
-                    if (ci < S.nunits) {
-                        if (l < 32) {
-#pragma unroll
-                            for (int m = 0; m < kMaxFusedM; ++m)
-                                if (m < p.M)
-                                    __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + l, acc[m],
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                        }
-                        if (l == 0)
-                            __hip_atomic_fetch_add(&ctl->arrived[par][ci], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    }
-                    acc = (v16i){};
-                    ++ci;
-                }
+            if (failed && !was && l == 0) {
+                __hip_atomic_store(&ctl->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+
+        // ---- contraction with the 16x16x64 MFMA: the tokens (at most four) are rows of A, a
+        //      tile's 32 weight rows are the columns of B in two halves (nb), its 128 columns two
+        //      k-blocks (kb): four MFMAs of 4 passes per tile, where the 32x32x32 form, whose
+        //      operand layout the packed tile has, takes four of 8 passes.  The tile sits in LDS,
+        //      so each lane simply reads the dwords that form needs: lane (n = l%16, kq = l/16)
+        //      wants weight row nb*16+n, columns kb*64 + kq*16 + 0..15, which the packed layout
+        //      keeps in dword kb*2 + kq/2 of the 16 bytes of lane (nb*16 + n) + 32*(kq%2).
+        //      A wavefront issues its MFMAs and its other vector instructions one after the other
+        //      (the other contracting wavefront of the SIMD fills the gaps), so everything that is
+        //      not contraction is kept out of the step: scalar conditions, no branches but the
+        //      rare waits, ring bookkeeping every fourth step.  The operands of the next step are
+        //      read from LDS while this step computes.
+        int *tiles = reinterpret_cast<int *>(lds + p.tile_off) + par * kMaxUnits * kMaxFusedM * kTileRows;
+        const int n16 = l & 15, kq = l >> 4;
+        const unsigned char *tlane = lds + p.ring_off + (size_t)w * p.ring_slots * kTileBytes +
+                                     (n16 + 32 * (kq & 1)) * 16 + (kq >> 1) * 4;
+        const int xbase = (n16 < p.M ? n16 : 0) * p.xstride + kq * 16;    // this lane's token row
+        const int zbase = p.jx_off + kMaxFusedM * 1024 + kq * 16;         // 128 bytes of zeros
+        const int total = S.nunits * S.TPW;
+        const unsigned long long token_rows = __builtin_amdgcn_ballot_w64(n16 < p.M);
+        unsigned long long exec_save;
+        struct Ops {
+            unsigned t[2][2];           // [nb][kb]: 16 two-bit codes each
+            v4i x[2];                   // [kb]: 16 quantised columns of the lane's token
+        };
+        Ops o0, o1;
+        // requests the operands of step `st` (k-turn j of its row-block): the tile's dwords from
+        // the ring (waiting, if the contraction has caught up with the loader, until the tile has
+        // landed) and the tokens' columns -- zeros where the row-block has no k-tile for this
+        // wavefront in its last turn, so that the MFMAs need no condition.  Past the phase's last
+        // step the requests still go out, to addresses that are valid and hold nothing of
+        // interest: requests under a condition would make every wait on LDS a wait for all.
+        auto operands = [&](Ops &o, int j, int st) __attribute__((always_inline)) {
+            const bool real = st < total;
+            if (__builtin_expect(real && known < gs + st + 1, 0)) {
+                int spins = 0;
+#pragma clang loop unroll(disable)
+                do {
+                    known = lds_load(&ctl->ready[w]);
+                    if (++spins >= kLdsPolls) failed = true;
+                } while (known < gs + st + 1 && !failed);
+            }
+            const unsigned char *ta = tlane + slot * kTileBytes;
+            o.t[0][0] = *reinterpret_cast<const unsigned *>(ta);
+            o.t[0][1] = *reinterpret_cast<const unsigned *>(ta + 8);
+            o.t[1][0] = *reinterpret_cast<const unsigned *>(ta + 256);
+            o.t[1][1] = *reinterpret_cast<const unsigned *>(ta + 264);
+            const int next = slot + 1 == p.ring_slots ? 0 : slot + 1;
+            slot = real ? next : slot;
+            const int kt = j * kStream + w;
+            const unsigned char *xa = lds + (kt < S.KT ? xbase + kt * kTileCols : zbase);
+            // Only the lanes of the tokens' rows read: a read by all 64 lanes costs LDS 16 times
+            // the bandwidth, and LDS is what the eight contracting wavefronts share.  The lanes are
+            // switched off around the reads by hand: a branch would make the compiler wait here for
+            // the requests just made.  It does not see these reads, so the step waits for them itself.
+            asm volatile("s_mov_b64 %[save], exec\n\t"
+                         "s_mov_b64 exec, %[rows]\n\t"
+                         "ds_read_b128 %[a], %[at]\n\t"
+                         "ds_read_b128 %[b], %[at] offset:64\n\t"
+                         "s_mov_b64 exec, %[save]"
+                         : [a] "=&v"(o.x[0]), [b] "=&v"(o.x[1]), [save] "=&s"(exec_save)
+                         : [at] "v"(lds_offset(xa)), [rows] "s"(token_rows)
+                         : "memory");
+        };
+        int ci = 0, cj = 0;
+        v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};      // weight rows 0..15 and 16..31 of the unit; element m: token m
+        // one step: request the next step's operands into the other register set, then contract
+        // this step's (two named sets, taken in turn: copying one set into the other would wait
+        // for the requests just made and undo the overlap)
+        auto step = [&](const Ops &oc, Ops &on, int st) __attribute__((always_inline)) {
+            const int nj = cj + 1 == S.TPW ? 0 : cj + 1;
+            __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): this step's operands, requested a step ago
+            __builtin_amdgcn_sched_barrier(0);
+            operands(on, nj, st + 1);
+            __builtin_amdgcn_sched_barrier(0);      // (the requests stay ahead of the MFMAs)
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[0], widen_codes(oc.t[0][0]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[0], widen_codes(oc.t[1][0]), acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[1], widen_codes(oc.t[0][1]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[1], widen_codes(oc.t[1][1]), acc1, 0, 0, 0);
+            cj = nj;
+            if ((st & 3) == 3 || nj == 0) {         // tell the loader what it may overwrite
+                if (l == 0) __hip_atomic_store(&ctl->consumed[w], gs + st + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            if (nj == 0) {
+                if (l < 16) {           // lanes 0..15 hold tokens 0..3 of weight rows l (acc0) and 16 + l (acc1)
+#pragma unroll
+                    for (int m = 0; m < kMaxFusedM; ++m)
+                        if (m < p.M) {
+                            __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + l, acc0[m], __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                            __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + 16 + l, acc1[m], __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                        }
+                }
+                if (l == 0)
+                    __hip_atomic_fetch_add(&ctl->arrived[par][ci], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                acc0 = (v4i){0, 0, 0, 0};
+                acc1 = (v4i){0, 0, 0, 0};
+                ++ci;
+            }
+        };
+        operands(o0, 0, 0);
+        for (int st = 0; st < total; st += 2) {
+            step(o0, o1, st);
+            if (st + 1 < total) step(o1, o0, st + 1);
+        }
+        gs += total;
     }
 }
 
@@ -373,6 +475,7 @@ __device__ __forceinline__ void job_xfetch(JobX &x, unsigned char *jxl, rsrc_t x
     const bool mine = kpb + (l >> 3) < kp1 && col < K;
     v4u v[MT];
     int polls = 0;
+#pragma clang loop unroll(disable)
     while (true) {
         bool ready = true;
 #pragma unroll
@@ -562,6 +665,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
         if (S.nunits > 0) {
             // this parity's rows were last read by the unit wavefront two phases ago
             int spins = 0;
+#pragma clang loop unroll(disable)
             while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
                 if (++spins >= kLdsPolls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
@@ -589,17 +693,17 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                 const unsigned at = mo + (unsigned)idx * 16u;
                 const unsigned step = (unsigned)p.M * hstride * 4u;
                 v4f h = {0.f, 0.f, 0.f, 0.f};
-                // all slices of the lane's four sums are requested at once; two sizes of that batch,
-                // because a try costs as many requests and comparisons as the batch is long
-                auto gather = [&](auto ns) __attribute__((always_inline)) {
-                    constexpr int NS = decltype(ns)::value;
-                    v4f part[NS];
+                // the slices of the lane's four sums, eight to a batch of requests (a try costs as
+                // many requests and comparisons as the batch is long), added in slice order
+                for (int s0 = 0; s0 < Sn; s0 += 8) {
+                    v4f part[8];
                     int polls = 0;
+#pragma clang loop unroll(disable)
                     while (true) {
                         bool ready = true;
 #pragma unroll
-                        for (int sl = 0; sl < NS; ++sl) {
-                            const v4u raw = load16_agent(mail, at + (unsigned)sl * step, wanted && sl < Sn);
+                        for (int sl = 0; sl < 8; ++sl) {
+                            const v4u raw = load16_agent(mail, at + (unsigned)(s0 + sl) * step, wanted && s0 + sl < Sn);
                             ready = ready && !has_sentinel(raw);
                             part[sl] = __builtin_bit_cast(v4f, raw);
                         }
@@ -610,12 +714,9 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                         }
                         __builtin_amdgcn_s_sleep(1);
                     }
-                    h = part[0];
 #pragma unroll
-                    for (int sl = 1; sl < NS; ++sl) h += part[sl];          // slice order: deterministic
-                };
-                if (Sn <= 8) gather(std::integral_constant<int, 8>{});
-                else gather(std::integral_constant<int, kSplit>{});
+                    for (int sl = 0; sl < 8; ++sl) h += part[sl];   // (slices past the last one were read as zero)
+                }
                 if (inside) {
                     v4h o;
 #pragma unroll
@@ -676,6 +777,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         if (S.nunits > 0) {
             // ---- SiLU(A x) of the phase is in LDS once the slice wavefront says so
             int spins = 0;
+#pragma clang loop unroll(disable)
             while (!failed && lds_load(&ctl->h_ready) < ph + 1) {
                 if (++spins >= kLdsPolls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
@@ -691,6 +793,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 const unsigned swb = gg == 0 ? swb0 : (gg == 1 ? swb1 : (gg == 2 ? swb2 : swb3));
                 const int hstride = gg == 0 ? hs0 : (gg == 1 ? hs1 : (gg == 2 ? hs2 : hs3));
                 int polls = 0;
+#pragma clang loop unroll(disable)
                 while (!failed && lds_load(&ctl->arrived[par][i]) < kStream) {
                     if (++polls >= kLdsPolls) {
                         failed = true;
@@ -782,7 +885,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
 // watch the code object when changing this kernel: indexing the arguments at run-time
 // offsets can make the compiler copy all 4 KiB of them into private memory -- it does with
 // a ring of more than 8 tiles -- and the kernel then crawls.)
-__global__ __launch_bounds__(512) void stack_kernel(const StackParams p)
+__global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ Control ctl;
@@ -791,16 +894,32 @@ __global__ __launch_bounds__(512) void stack_kernel(const StackParams p)
     // everything the two sides add into or count with starts at zero; afterwards the service
     // wavefront resets what it has consumed
     int *tiles = reinterpret_cast<int *>(lds + p.tile_off);
-    for (int e = threadIdx.x; e < 2 * kMaxUnits * kMaxFusedM * kTileRows; e += 512) tiles[e] = 0;
-    for (int e = threadIdx.x; e < (int)(sizeof(Control) / sizeof(int)); e += 512) reinterpret_cast<int *>(&ctl)[e] = 0;
+    for (int e = threadIdx.x; e < 2 * kMaxUnits * kMaxFusedM * kTileRows; e += 64 * kWaves) tiles[e] = 0;
+    for (int e = threadIdx.x; e < (int)(sizeof(Control) / sizeof(int)); e += 64 * kWaves) reinterpret_cast<int *>(&ctl)[e] = 0;
+    if (threadIdx.x < 32) reinterpret_cast<int *>(lds + p.jx_off + kMaxFusedM * 1024)[threadIdx.x] = 0;
     __syncthreads();
-    if (w == kStream) slice_wave(p, lds, &ctl, c);
-    else if (w == kStream + 1) unit_wave(p, lds, &ctl, c);
-    else streaming_wave(p, lds, &ctl, c);
+    if (w < kStream) {
+        contract_wave(p, lds, &ctl, c);
+    } else if (w < kStream + kLoaders) {
+        loader_wave(p, lds, &ctl, c, w - kStream);
+    } else {
+        // the two serving wavefronts share their SIMDs with contracting ones and are the ones
+        // every other workgroup waits for: they issue first
+#ifndef HGF_PRIO
+#define HGF_PRIO 2
+#endif
+        if (w == kStream + kLoaders) {
+            if (HGF_PRIO & 1) __builtin_amdgcn_s_setprio(3);
+            slice_wave(p, lds, &ctl, c);
+        } else {
+            if (HGF_PRIO & 2) __builtin_amdgcn_s_setprio(3);
+            unit_wave(p, lds, &ctl, c);
+        }
+    }
 }
 
 int g_num_cus = 0;
-constexpr size_t kStackLdsMax = 144 * 1024;
+constexpr size_t kStackLdsMax = 156 * 1024;   // (the compute unit has 160 KiB; the control words are static)
 
 }  // namespace
 
@@ -866,19 +985,28 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
     off += (size_t)2 * p.h_par;
     off = (off + 1023) & ~size_t(1023);
     p.jx_off = (int)off;                                          // the slice wavefront's pieces of the tokens
-    off += (size_t)kMaxFusedM * 1024;
+    off += (size_t)kMaxFusedM * 1024 + 1024;                      // ... and 128 bytes of zeros (kept 1 KiB aligned)
     p.unit_off = (int)off;
     p.unit_alpha = 64 * hstride_max;
     p.unit_stride = p.unit_alpha + 256;
     off += (size_t)per_wg * p.unit_stride;
+    // the rest holds the rings of weight tiles: the deeper, the longer the loaders keep the
+    // memory busy while a phase waits for its tokens
+    if (off + (size_t)kStream * kMinRing * kTileBytes > kStackLdsMax) return false;
+    int slots = (int)((kStackLdsMax - off) / ((size_t)kStream * kTileBytes));
+    if (slots > kMaxRing) slots = kMaxRing;
+    p.ring_off = (int)off;
+    p.ring_slots = slots;
+    off += (size_t)kStream * slots * kTileBytes;
     *lds_bytes = off;
-    return off <= kStackLdsMax;
+    return true;
 }
 
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st)
 {
-    hipLaunchKernelGGL(stack_kernel, dim3(p.nwg), dim3(512), lds_bytes, st, p);
+    hipLaunchKernelGGL(stack_kernel, dim3(p.nwg), dim3(64 * kWaves), lds_bytes, st, p);
     return hipGetLastError();
 }
 
 }  // namespace hgf
+
