@@ -154,6 +154,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
         float amax = 0.0f;
 #pragma unroll
         for (int u = 0; u < XU; ++u) {
+            if (4 * u >= S.TPW) continue;           // (no k-turn that far in this phase: nothing was read)
             const v8h a = __builtin_elementwise_abs(__builtin_bit_cast(v8h, v[m][u]));
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, (float)a[e]);
@@ -184,6 +185,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
         int sum = 0;
 #pragma unroll
         for (int u = 0; u < XU; ++u) {
+            if (4 * u >= S.TPW) continue;
             const int j = (l >> 4) + 4 * u;
             const int kt = j * kStream + w;
             const v8h x8 = __builtin_bit_cast(v8h, v[m][u]);        // columns past d_in were read as zero
