@@ -40,7 +40,7 @@ constexpr int kLoaders = 2;            // loader wavefronts (8, 9): each feeds f
 constexpr int kFeed = kStream / kLoaders;
 constexpr int kWaves = kStream + kLoaders + 2;
 #ifndef HGF_STACK_WINDOW
-#define HGF_STACK_WINDOW 6
+#define HGF_STACK_WINDOW 3
 #endif
 constexpr int kWindow = HGF_STACK_WINDOW;   // groups of kFeed weight tiles a loader keeps in flight
 constexpr int kMinRing = kWindow + 4;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow)
