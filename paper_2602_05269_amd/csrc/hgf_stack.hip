@@ -6,17 +6,19 @@
 // (one per compute unit) stay resident for the whole list and walk it phase by phase -- a
 // phase is a group of up to four layers that read the same activations:
 //
-//   * seven streaming wavefronts keep a ring of weight tiles in flight across phase
-//     boundaries: weights do not depend on activations, so while a phase waits for its input
-//     the memory system keeps delivering its first tiles.  Wavefront w contracts the k-tiles
-//     w, w+7, ... of every row-block, so it fetches and quantises exactly those columns of the
-//     tokens itself; the seven meet once per phase, for the per-token absmax;
-//   * one service wavefront computes its slice of A x from the columns that slice needs,
-//     collects all slices, and finishes the units its workgroup owns (dequantise, B h, gate,
-//     store).  It shares no barrier with the streaming side: the two meet through counters
-//     in LDS.
+//   * two loader wavefronts stream the weight tiles into rings in LDS, phase after phase as
+//     far ahead as the rings reach: weights do not depend on activations, so while a phase
+//     waits for its input the memory system keeps delivering its tiles;
+//   * eight contracting wavefronts (two per SIMD): wavefront w contracts the k-tiles w, w+8,
+//     ... of every row-block, so it fetches and quantises exactly those columns of the tokens
+//     itself; the eight meet once per phase, for the per-token absmax;
+//   * the slice wavefront computes its slice of A x from the columns that slice needs,
+//     collects all slices and puts SiLU of their sum into LDS;
+//   * the unit wavefront finishes the units its workgroup owns (dequantise, B h, gate, store).
+//   No wavefront takes part in a workgroup barrier after the first instruction: the roles
+//   meet through counters in LDS.
 //
-// Activations pass from one phase to the next through the workspace: the service wavefronts
+// Activations pass from one phase to the next through the workspace: the unit wavefronts
 // store every output both to the caller's slot and, with device scope, to an exchange
 // region that holds a sentinel bit pattern (all ones) wherever nothing has been written;
 // readers re-read with device scope until no word is the sentinel.  No flag, no fence, no
