@@ -59,14 +59,14 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 struct Control {                       // LDS words shared by the two sides; [2]: one set per phase parity
-    int arrived[2][kMaxUnits];         // streaming wavefronts that have posted the unit (the service side resets it)
+    int arrived[2][kMaxUnits];         // contracting wavefronts that have posted the unit (the unit wavefront resets it)
     int rowsum_part[2][kStream][kMaxFusedM];   // sums of the quantised columns each wavefront owns
     float amax_part[2][kStream][kMaxFusedM];   // absmax of those columns
     float sx[2][kMaxFusedM];
     int sync;                          // absmax parts posted, summed over the phases
     int svc_done;                      // phases whose units the unit wavefront has finished
     int h_ready;                       // phases whose SiLU(A x) the slice wavefront has put into LDS
-    int failed;                        // a wait of the streaming side has expired
+    int failed;                        // a wait of a loader, contracting or slice wavefront has expired
     int ready[kStream];                // weight tiles of the wavefront's ring that have landed in LDS, in all
     int consumed[kStream];             // ... and how many of them it has read
 };
@@ -114,7 +114,7 @@ __device__ __forceinline__ PhaseShape shape_of(const StackParams &p, int ph, int
     s.nunits = c < s.units ? (s.units - c + p.nwg - 1) / p.nwg : 0;
     return s;
 }
-// ------------------------------------------------------------------ streaming side
+// ------------------------------------------------------------------ loaders and contracting wavefronts
 // Per-token absmax int8 quantisation (Sec. 2.2.1) of the columns wavefront w contracts: the
 // k-tiles w, w+8, ... (128 columns each).  The columns come from the caller's slot or, once
 // no word of them is the sentinel, from the exchange region; they stay in registers between
@@ -170,7 +170,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     while (!failed && lds_load(&ctl->sync) < sync_target) {
         if (++polls >= kLdsPolls) failed = true;
     }
-    // what this phase shares with the service side was last used two phases ago
+    // what this phase shares with the unit wavefront was last used two phases ago
     polls = 0;
 #pragma clang loop unroll(disable)
     while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
@@ -443,7 +443,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
     }
 }
 
-// ------------------------------------------------------------------ service side
+// ------------------------------------------------------------------ slice and unit wavefronts
 struct JobRegs {
     v8h a[kUN][2];
 };
@@ -810,7 +810,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 int a[kMaxFusedM];
 #pragma unroll
                 for (int m = 0; m < kMaxFusedM; ++m) a[m] = tiles[(i * kMaxFusedM + m) * kTileRows + jl];
-                if (i == 0) {           // every streaming wavefront has posted: so are the tokens' sums and scales
+                if (i == 0) {           // every contracting wavefront has posted: so are the tokens' sums and scales
 #pragma unroll
                     for (int m = 0; m < kMaxFusedM; ++m) {
                         rs[m] = 0;
@@ -895,7 +895,7 @@ __global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
     __shared__ Control ctl;
     const int c = blockIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // everything the two sides add into or count with starts at zero; afterwards the service
+    // everything the roles add into or count with starts at zero; afterwards the unit
     // wavefront resets what it has consumed
     int *tiles = reinterpret_cast<int *>(lds + p.tile_off);
     for (int e = threadIdx.x; e < 2 * kMaxUnits * kMaxFusedM * kTileRows; e += 64 * kWaves) tiles[e] = 0;
