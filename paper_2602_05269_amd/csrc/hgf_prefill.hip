@@ -21,9 +21,7 @@ namespace hgf {
 namespace {
 
 constexpr int kPN = 256;            // output rows per workgroup: four wavefronts x two row-blocks
-constexpr int kPM = 128;            // tokens per workgroup
-constexpr int kPG = kPM / 32;       // token groups of 32 per wavefront
-constexpr int kXP = kPM * kTileCols / (256 * 16);   // 16-byte activation pieces per thread and step
+constexpr int kPM = 128;            // tokens per workgroup at most (the LDS buffers hold that many)
 
 struct PrefillParams {
     const v4u *packed;
@@ -51,9 +49,16 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 __device__ inline unsigned piece_slot(unsigned piece, unsigned row) { return piece ^ ((row >> 1) & 7u); }
 
 // JS: steps of the 32x32x16 f16 MFMA over the (padded) rank = hstride / 16; 0 without correction.
-template <int JS>
+// PM: tokens per workgroup, 128 or 64.  A wavefront issues its MFMAs and its other vector
+// instructions one after the other, so a compute unit needs two workgroups in residence for
+// one's MFMAs to overlap the other's unpacking and LDS reads; a layer whose 256 x 128 tiles
+// number fewer than that is cut into 256 x 64 tiles (each widened weight operand then feeds two
+// MFMAs instead of four, each activation operand still two).
+template <int JS, int PM>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 {
+    constexpr int kPG = PM / 32;                         // token groups of 32 per wavefront
+    constexpr int kXP = PM * kTileCols / (256 * 16);     // 16-byte activation pieces per thread and step
     // four separately declared activation buffers: the compiler can then prove that an
     // LDS-direct load into one does not alias the reads of another and leaves it in flight
     __shared__ __attribute__((aligned(1024))) unsigned char xs0[kPM * kTileCols];
@@ -66,8 +71,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nb = blockIdx.x % p.NB, mb = blockIdx.x / p.NB;
     const int rb0 = nb * (kPN / kTileRows) + w * 2;      // this wavefront's first row-block
-    const int m0 = mb * kPM;
-    const int mrows = min(kPM, p.M - m0);
+    const int m0 = mb * PM;
+    const int mrows = min(PM, p.M - m0);
 
     rsrc_t wr[2];
 #pragma unroll
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     // ---- epilogue: correction up-projection on the f16 MFMA, gate, dequantise, store.
     //      Element 4*q + v of an accumulator is row 8*q + 4*hf + v of the row-block, for the
     //      token of the lane.
-    // SiLU(A x) of the 128 tokens goes into the (now free) activation buffers, tokens 0..63
+    // SiLU(A x) of the tokens goes into the (now free) activation buffers, tokens 0..63
     // into xs0 and 64..127 into xs1, rows of JS*32 bytes with the same XOR permutation of the
     // 16-byte pieces; the B rows of both row-blocks go to registers.  All of it is requested
     // in one burst: one memory round trip for the whole epilogue.
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     if (JS > 0) {
         const rsrc_t hr = make_rsrc(p.h16 + (size_t)m0 * p.hstride, (unsigned)mrows * p.hstride * 2u);
 #pragma unroll
-        for (int buf = 0; buf < 2; ++buf) {
+        for (int buf = 0; buf < PM / 64; ++buf) {
 #pragma unroll
             for (int i = 0; i < JS / 2; ++i) {
                 const unsigned byte = (unsigned)(4 * i + w) * 1024 + l * 16;
@@ -318,14 +323,33 @@ hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const
     p.rank = L.rank;
     p.hstride = h_stride(L.rank > 0 ? L.rank : 1);
     p.NB = (L.d_out + kPN - 1) / kPN;
-    const int MB = (M + kPM - 1) / kPM;
-    const dim3 grid(p.NB * MB), block(256);
-    switch (L.rank > 0 ? p.hstride / 16 : 0) {
-        case 0: hipLaunchKernelGGL(prefill_kernel<0>, grid, block, 0, st, p); break;
-        case 2: hipLaunchKernelGGL(prefill_kernel<2>, grid, block, 0, st, p); break;
-        case 4: hipLaunchKernelGGL(prefill_kernel<4>, grid, block, 0, st, p); break;
-        default: hipLaunchKernelGGL(prefill_kernel<8>, grid, block, 0, st, p); break;
+    static int num_cus = 0;
+    if (num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        num_cus = n;
     }
+    // fewer 256 x 128 tiles than two per compute unit: 256 x 64 tiles, twice as many workgroups
+    const bool narrow = p.NB * ((M + kPM - 1) / kPM) < 2 * num_cus;
+    const int pm = narrow ? 64 : kPM;
+    const int MB = (M + pm - 1) / pm;
+    const dim3 grid(p.NB * MB), block(256);
+#define HGF_PREFILL(JS)                                                                        \
+    do {                                                                                       \
+        if (narrow) hipLaunchKernelGGL((prefill_kernel<JS, 64>), grid, block, 0, st, p);       \
+        else hipLaunchKernelGGL((prefill_kernel<JS, 128>), grid, block, 0, st, p);             \
+    } while (0)
+    switch (L.rank > 0 ? p.hstride / 16 : 0) {
+        case 0: HGF_PREFILL(0); break;
+        case 2: HGF_PREFILL(2); break;
+        case 4: HGF_PREFILL(4); break;
+        default: HGF_PREFILL(8); break;
+    }
+#undef HGF_PREFILL
     return hipGetLastError();
 }
 
