@@ -796,6 +796,21 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 const StackLayer &Lg = L[gg];
                 const unsigned swb = gg == 0 ? swb0 : (gg == 1 ? swb1 : (gg == 2 ? swb2 : swb3));
                 const int hstride = gg == 0 ? hs0 : (gg == 1 ? hs1 : (gg == 2 ? hs2 : hs3));
+                // the correction term needs only SiLU(A x) and the staged operands: it is computed
+                // before the wait for the contraction, so that after the last unit's contraction
+                // only the sums, one multiply-add per output and the stores remain
+                v16f corr = (v16f){};
+                float gate = 0.f;
+                if (Lg.rank > 0) {
+                    gate = tanh_fast((float)*reinterpret_cast<const _Float16 *>(op + p.unit_alpha + jl * 2));
+                    const _Float16 *hrow = hs + (gg * p.M + jl) * kHsStride + hf * 8;
+                    const unsigned char *brow = op + (hf * 32 + jl) * 16;
+                    switch (hstride / 16) {
+                        case 2: corr = corr_unit<2>(hrow, brow, jl < p.M); break;
+                        case 4: corr = corr_unit<4>(hrow, brow, jl < p.M); break;
+                        default: corr = corr_unit<8>(hrow, brow, jl < p.M); break;
+                    }
+                }
                 int polls = 0;
 #pragma clang loop unroll(disable)
                 while (!failed && lds_load(&ctl->arrived[par][i]) < kStream) {
@@ -823,18 +838,6 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 for (int m = 0; m < kMaxFusedM; ++m)
                     if (l < 32) tiles[(i * kMaxFusedM + m) * kTileRows + l] = 0;
                 if (l == 0) ctl->arrived[par][i] = 0;
-                v16f corr = (v16f){};
-                float gate = 0.f;
-                if (Lg.rank > 0) {
-                    gate = tanh_fast((float)*reinterpret_cast<const _Float16 *>(op + p.unit_alpha + jl * 2));
-                    const _Float16 *hrow = hs + (gg * p.M + jl) * kHsStride + hf * 8;
-                    const unsigned char *brow = op + (hf * 32 + jl) * 16;
-                    switch (hstride / 16) {
-                        case 2: corr = corr_unit<2>(hrow, brow, jl < p.M); break;
-                        case 4: corr = corr_unit<4>(hrow, brow, jl < p.M); break;
-                        default: corr = corr_unit<8>(hrow, brow, jl < p.M); break;
-                    }
-                }
                 const int n = n0 + l;
                 const float s_w = __builtin_bit_cast(float, swb);
                 const int Npad = (Lg.N + 7) & ~7;         // row pitch of the exchange copy (16-byte rows)
