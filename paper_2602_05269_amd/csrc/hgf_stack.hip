@@ -129,6 +129,10 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     const int l = threadIdx.x & 63, par = ph & 1;
     constexpr int XU = 3;               // 64 lanes x 3 pieces of 8 columns = 12 tiles of a token
     const int pc = l & 15;
+    // what this phase shares with the unit wavefront was last used two phases ago; looked at
+    // here, where the wavefront is about to wait for memory anyway, and waited for (rarely)
+    // after the tokens have come
+    bool unit_done = lds_load(&ctl->svc_done) >= ph - 1;
     v4u v[MT][XU];
     int polls = 0;
 #pragma clang loop unroll(disable)
@@ -170,10 +174,10 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     while (!failed && lds_load(&ctl->sync) < sync_target) {
         if (++polls >= kLdsPolls) failed = true;
     }
-    // what this phase shares with the unit wavefront was last used two phases ago
     polls = 0;
 #pragma clang loop unroll(disable)
-    while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
+    while (!unit_done && !failed) {
+        unit_done = lds_load(&ctl->svc_done) >= ph - 1;
         if (++polls >= kLdsPolls) failed = true;
         __builtin_amdgcn_s_sleep(1);
     }
@@ -820,11 +824,13 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                     }
                     __builtin_amdgcn_s_sleep(1);
                 }
-                if (lds_load(&ctl->failed) != 0) failed = true;
-                // the unit's sums, then this parity's words are ready for the phase after next
+                // the unit's sums (and whether a wait of another wavefront has expired), then this
+                // parity's words are ready for the phase after next
+                const int others_failed = __hip_atomic_load(&ctl->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 int a[kMaxFusedM];
 #pragma unroll
                 for (int m = 0; m < kMaxFusedM; ++m) a[m] = tiles[(i * kMaxFusedM + m) * kTileRows + jl];
+                if (others_failed != 0) failed = true;
                 if (i == 0) {           // every contracting wavefront has posted: so are the tokens' sums and scales
 #pragma unroll
                     for (int m = 0; m < kMaxFusedM; ++m) {
