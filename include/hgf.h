@@ -174,6 +174,15 @@ void hgf_set_decode_target_workgroups(int n);
  * integers; the fp16 outputs may differ in the last place (different split of A x). */
 void hgf_set_single_launch(int level);
 
+/* Test hook (host state, not thread-safe) for the whole-stack launch of hgf_stack_forward, in
+ * which workgroups wait for each other's results: every such wait gives up after a bounded
+ * number of tries (by default about a second), sets the sticky error word of the workspace
+ * (byte offset 8, cleared by hgf_workspace_init), turns the affected outputs into NaN and lets
+ * the kernel run to its end.  tries > 0 replaces the bound of every wait by that many tries, so
+ * that a test can see the give-up path without anything having to go wrong; 0 restores the
+ * default.  Never needed in production. */
+void hgf_set_wait_limit(int tries);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.hgf_set_decode_target_workgroups.argtypes = [ci]
     L.hgf_set_single_launch.restype = None
     L.hgf_set_single_launch.argtypes = [ci]
+    L.hgf_set_wait_limit.restype = None
+    L.hgf_set_wait_limit.argtypes = [ci]
     L.hgf_profile_enable.restype = None
     L.hgf_profile_enable.argtypes = [ci]
     L.hgf_profile_collect.restype = ci
@@ -134,6 +136,12 @@ def hgf_workspace_init(ws: Workspace, stream=None) -> None:
 def hgf_set_single_launch(level) -> None:
     """0: two launches per group; 1 (or True): one persistent launch per group; 2: per stack."""
     lib().hgf_set_single_launch(int(level))
+
+
+def hgf_set_wait_limit(tries: int) -> None:
+    """Test hook: every wait between workgroups of the whole-stack launch gives up after `tries`
+    tries (0: the default bound of about a second)."""
+    lib().hgf_set_wait_limit(int(tries))
 
 
 def hgf_set_decode_target_workgroups(n: int) -> None:

@@ -480,4 +480,6 @@ void hgf_set_decode_target_workgroups(int n) { set_decode_target_wgs(n); }
 
 void hgf_set_single_launch(int level) { g_launch_level = level < 0 ? 0 : (level > 2 ? 2 : level); }
 
+void hgf_set_wait_limit(int tries) { set_stack_wait_limit(tries); }
+
 }  // extern "C"

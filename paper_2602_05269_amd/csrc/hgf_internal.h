@@ -244,6 +244,7 @@ struct StackParams {
     unsigned char *xchg;          // two sets of kStackSetBytes
     unsigned act_used, mail_used;
     int xstride, h_par, tile_off, h_off, unit_off, unit_stride, unit_alpha, jx_off, ring_off, ring_slots;   // LDS layout
+    int mem_polls, lds_polls;     // tries after which a wait for another workgroup / another wavefront gives up
     StackPhase ph[kStackMaxPhases];
     StackLayer L[kStackMaxLayers];
 };
@@ -265,6 +266,7 @@ bool plan_fused(FusedParams &p, size_t *lds_bytes);
 hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);
 int decode_target_waves();
 bool plan_stack(StackParams &p, size_t *lds_bytes);
+void set_stack_wait_limit(int tries);
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
 void set_decode_target_wgs(int v);
 hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const hgf_layer &L, _Float16 *y,

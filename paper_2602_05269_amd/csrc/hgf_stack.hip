@@ -48,8 +48,8 @@ constexpr int kWindow = HGF_STACK_WINDOW;   // groups of kFeed weight tiles a lo
 constexpr int kMinRing = kWindow + 4;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow)
 constexpr int kMaxRing = 48;
 constexpr int kMaxUnits = 16;          // units per workgroup and phase at most
-constexpr int kLdsPolls = 1 << 22;     // bound of a wait on LDS (about a second)
-constexpr int kMemPolls = 1 << 18;     // bound of a wait on an exchange region (about a second)
+constexpr int kLdsPollsDefault = 1 << 22;   // bound of a wait on LDS (about a second)
+constexpr int kMemPollsDefault = 1 << 18;   // bound of a wait on an exchange region (about a second)
 constexpr unsigned kSentinel = 0xFFFFFFFFu;
 constexpr int kHsStride = HGF_MAX_RANK;  // halves per (layer, token) row of SiLU(A x) in LDS
 constexpr int kUN = 8;                 // 64-column steps of a slice of A x requested together
@@ -149,7 +149,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
             }
         }
         if (ext || failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
-        if (++polls >= kMemPolls) {
+        if (++polls >= p.mem_polls) {
             failed = true;
             break;
         }
@@ -172,13 +172,13 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     polls = 0;
 #pragma clang loop unroll(disable)
     while (!failed && lds_load(&ctl->sync) < sync_target) {
-        if (++polls >= kLdsPolls) failed = true;
+        if (++polls >= p.lds_polls) failed = true;
     }
     polls = 0;
 #pragma clang loop unroll(disable)
     while (!unit_done && !failed) {
         unit_done = lds_load(&ctl->svc_done) >= ph - 1;
-        if (++polls >= kLdsPolls) failed = true;
+        if (++polls >= p.lds_polls) failed = true;
         __builtin_amdgcn_s_sleep(1);
     }
 #pragma unroll
@@ -275,7 +275,7 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
 #pragma unroll
                         for (int f = 1; f < kFeed; ++f) freed = min(freed, lds_peek(cons_at + 4u * f));
                         if (n - freed < p.ring_slots) break;
-                        if (++spins >= kLdsPolls || lds_peek(failed_at) != 0) failed = true;
+                        if (++spins >= p.lds_polls || lds_peek(failed_at) != 0) failed = true;
                         __builtin_amdgcn_s_sleep(2);
                     }
                 }
@@ -376,7 +376,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
 #pragma clang loop unroll(disable)
                 do {
                     known = lds_load(&ctl->ready[w]);
-                    if (++spins >= kLdsPolls) failed = true;
+                    if (++spins >= p.lds_polls) failed = true;
                 } while (known < gs + st + 1 && !failed);
             }
             const unsigned char *ta = tlane + slot * kTileBytes;
@@ -476,7 +476,7 @@ struct JobX {
 };
 template <int MT>
 __device__ __forceinline__ void job_xfetch(JobX &x, unsigned char *jxl, rsrc_t xr, bool ext, int M, int K, int kpb,
-                                           int kp1, bool &failed)
+                                           int kp1, int mem_polls, bool &failed)
 {
     const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
     const int col = kpb * 64 + l * 8;
@@ -492,7 +492,7 @@ __device__ __forceinline__ void job_xfetch(JobX &x, unsigned char *jxl, rsrc_t x
             ready = ready && !has_sentinel(v[m]);
         }
         if (ext || failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
-        if (++polls >= kMemPolls) {
+        if (++polls >= mem_polls) {
             failed = true;
             break;
         }
@@ -654,9 +654,9 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             JobX jx;
             for (int kpb = kp0; kpb < kp1; kpb += kUN) {
                 if (kpb > kp0) job_load(jr, jA, jrank, S.K, rt, kpb, kp1);
-                if (p.M == 1) job_xfetch<1>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, failed);
-                else if (p.M == 2) job_xfetch<2>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, failed);
-                else job_xfetch<4>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, failed);
+                if (p.M == 1) job_xfetch<1>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
+                else if (p.M == 2) job_xfetch<2>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
+                else job_xfetch<4>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
                 acc = job_mfma(jr, jx, acc);
             }
             // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of the layer
@@ -675,7 +675,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             int spins = 0;
 #pragma clang loop unroll(disable)
             while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
-                if (++spins >= kLdsPolls) failed = true;
+                if (++spins >= p.lds_polls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
             }
             // ---- collect every slice: h[g][m][j] = SiLU(sum_sp partial) (step 6); a lane takes four
@@ -716,7 +716,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                             part[sl] = __builtin_bit_cast(v4f, raw);
                         }
                         if (failed || __builtin_amdgcn_ballot_w64(!ready) == 0) break;
-                        if (++polls >= kMemPolls) {
+                        if (++polls >= p.mem_polls) {
                             failed = true;
                             break;
                         }
@@ -787,7 +787,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
             int spins = 0;
 #pragma clang loop unroll(disable)
             while (!failed && lds_load(&ctl->h_ready) < ph + 1) {
-                if (++spins >= kLdsPolls) failed = true;
+                if (++spins >= p.lds_polls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
             }
             // ---- per unit: lane n < 32 owns output row n of the unit for every token
@@ -818,7 +818,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 int polls = 0;
 #pragma clang loop unroll(disable)
                 while (!failed && lds_load(&ctl->arrived[par][i]) < kStream) {
-                    if (++polls >= kLdsPolls) {
+                    if (++polls >= p.lds_polls) {
                         failed = true;
                         break;
                     }
@@ -932,6 +932,7 @@ __global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
 }
 
 int g_num_cus = 0;
+int g_wait_limit = 0;                  // 0: the default bounds
 constexpr size_t kStackLdsMax = 156 * 1024;   // (the compute unit has 160 KiB; the control words are static)
 
 }  // namespace
@@ -952,6 +953,8 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
         }
         g_num_cus = n > 0 ? n : 1;
     }
+    p.mem_polls = g_wait_limit > 0 ? g_wait_limit : kMemPollsDefault;
+    p.lds_polls = g_wait_limit > 0 ? g_wait_limit : kLdsPollsDefault;
     const int M = p.M;
     int kmax = 0, units_max = 0, jobs_max = 0, hstride_max = 32, gmax = 1;
     size_t mail = 0;
@@ -1014,6 +1017,8 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
     *lds_bytes = off;
     return true;
 }
+
+void set_stack_wait_limit(int tries) { g_wait_limit = tries > 0 ? tries : 0; }
 
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st)
 {

@@ -269,6 +269,46 @@ def test_mixed_stack_teacher_forced(M, ws):
         assert np.array_equal(slots[dst].cpu().numpy(), host[dst])
 
 
+def test_stack_waits_give_up_and_recover(ws):
+    """The give-up path of the whole-stack launch, forced from the host: with every wait between
+    workgroups cut to one try, a chained list cannot hand its activations on in time.  The
+    launch must still run to its end (no hang) and set the sticky error word; after
+    hgf_workspace_init and with the default bound the same list gives the oracle's results."""
+    M = 1
+    shapes = [(512, 1024, 16, 0, 1), (1024, 512, 16, 1, 2), (512, 768, 32, 2, 3), (768, 256, 8, 3, 4)]
+    cases, layers = [], []
+    slots = [None] * 5
+    for i, (K, N, r, src, dst) in enumerate(shapes):
+        c = synth.make_custom(7700 + i, M, K, N, r, act="student_t4", lora_std=0.05, w_std=0.05)
+        if i == 0:
+            slots[0] = dev(c["x"])
+        g = GpuLayer(c, ws)
+        g.layer.c.src_slot, g.layer.c.dst_slot = src, dst
+        cases.append(g)
+        layers.append(g.layer)
+        slots[dst] = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    st = hb.Stack(layers, slots, M)
+    flags = lambda: ws.buf[:32].view(torch.int32).cpu().numpy().copy()
+    hb.hgf_workspace_init(ws)
+    try:
+        hb.hgf_set_wait_limit(1)
+        hb.hgf_stack_forward(st, ws)
+        torch.cuda.synchronize()                    # returns: every wait was bounded
+    finally:
+        hb.hgf_set_wait_limit(0)
+    after = flags()
+    assert after[2] != 0 and after[5] == 0, after   # error word set, every workgroup reached the end
+    hb.hgf_workspace_init(ws)
+    for (_, _, _, _, dst) in shapes:
+        slots[dst].zero_()
+    hb.hgf_stack_forward(st, ws)
+    torch.cuda.synchronize()
+    assert flags()[2] == 0
+    host = [s_.cpu().numpy() for s_ in slots]
+    for g, (K, N, r, src, dst) in zip(cases, shapes):
+        assert_close_fp16(host[dst], g.oracle(host[src])["y"], f"slot {dst}")
+
+
 # ------------------------------------------------------------------ full-size configurations, sampled
 
 def _sampled(cfg, proj, M, ws, n_rows=96, n_tok=None):
