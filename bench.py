@@ -317,9 +317,9 @@ def main() -> int:
         # 3B-shape prefill layer, M=2048, the 7 projections of one block
         w3 = Workload(3, 2048, 1, seed=3000, ws=ws)
         s3 = time_steps(make_runner(w3, ws, False), 3, 1)
-        (_, _), (pms, pn) = kernel_profile(w3, ws, 2)
+        (_, _), (pms, pn) = kernel_profile(w3, ws, 2)      # two passes; the events bracket grouped launches
         tops = w3.int8_ops / s3 / 1e12
-        k_tops = w3.int8_ops / len(w3.layers) / (pms / 1e3 / max(pn, 1)) / 1e12 if pn else 0.0
+        k_tops = 2 * w3.int8_ops / (pms / 1e3) / 1e12 if pn else 0.0
         cases["config3_prefill_M2048"] = {"int8_TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4),
                                           "ms_per_layer": round(s3 * 1e3, 3),
                                           "main_kernel_int8_TOPS": round(k_tops, 1)}

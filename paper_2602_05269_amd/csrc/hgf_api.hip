@@ -183,8 +183,8 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
 }
 
 // Large M: per group of layers that read the same activations, one quantiser launch, one
-// launch of the down-projections with SiLU (all layers), then the int8 MFMA prefill kernel
-// per layer.
+// launch of the down-projections with SiLU (all layers), then one launch of the int8 MFMA
+// prefill kernel over the tiles of all layers.
 hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
                            int32_t *acc_debug, const Workspace &ws, hipStream_t st)
 {
@@ -200,13 +200,8 @@ hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G,
         h16[g] = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
     }
     if (launch_corr_down(xh, M, K, G, A, rank, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
-    for (int g = 0; g < G; ++g) {
-        ProfileScope prof(1, st);
-        const hgf_status s = from_hip(launch_prefill(ws, h16[g], M, layers[g], reinterpret_cast<_Float16 *>(ys[g]),
-                                                     acc_debug, st));
-        if (s != HGF_OK) return s;
-    }
-    return HGF_OK;
+    ProfileScope prof(1, st);
+    return from_hip(launch_prefill(ws, h16, M, layers, G, ys, acc_debug, st));
 }
 
 }  // namespace

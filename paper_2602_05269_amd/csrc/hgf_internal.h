@@ -269,7 +269,7 @@ bool plan_stack(StackParams &p, size_t *lds_bytes);
 void set_stack_wait_limit(int tries);
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
 void set_decode_target_wgs(int v);
-hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const hgf_layer &L, _Float16 *y,
-                          int32_t *acc_debug, hipStream_t st);
+hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
+                          void *const *ys, int32_t *acc_debug, hipStream_t st);
 
 }  // namespace hgf

@@ -11,7 +11,7 @@
 // Weights never touch LDS: a wavefront loads its own packed tiles (16 bytes per lane per
 // row-block per 128 columns), widens the 2-bit codes in registers and uses them as the
 // MFMA's row operand.  The quantised activations of the 128 tokens are loaded straight
-// into LDS (four buffers, requested three steps ahead, one barrier per 128 columns) and are
+// into LDS (four buffers, requested four steps ahead, one barrier per 128 columns) and are
 // shared by the four wavefronts.  Codes are T+1; the per-token sum of x_q is subtracted in
 // the epilogue (integer-exact).
 #include "hgf_internal.h"
@@ -23,19 +23,28 @@ namespace {
 constexpr int kPN = 256;            // output rows per workgroup: four wavefronts x two row-blocks
 constexpr int kPM = 128;            // tokens per workgroup at most (the LDS buffers hold that many)
 
-struct PrefillParams {
+struct PrefillLayer {
     const v4u *packed;
-    const int8_t *xq;
-    const float *s_x;
-    const int32_t *rowsum;
     const float *s_w;
     const _Float16 *B;
     const _Float16 *alpha;
     const _Float16 *h16;
     _Float16 *y;
-    int32_t *acc_debug;
-    int M, N, Kp, KT, RBn, rank, hstride;
-    int NB;                        // workgroups along the output rows
+    int N, RBn, rank;
+    int nb_start;                  // first of this layer's row tiles among the launch's
+};
+
+// One launch covers every layer of a group (layers that read the same activations): the tail of
+// one layer's tiles -- compute units left with a single workgroup, which does not keep the
+// matrix cores busy on its own -- fills up with the next layer's.
+struct PrefillParams {
+    const int8_t *xq;
+    const float *s_x;
+    const int32_t *rowsum;
+    int32_t *acc_debug;            // single-layer launches only
+    int M, Kp, KT, hstride, G;
+    int NB;                        // row tiles of all layers
+    PrefillLayer L[kMaxGroup];
 };
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -61,15 +70,19 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     constexpr int kXP = PM * kTileCols / (256 * 16);     // 16-byte activation pieces per thread and step
     // four separately declared activation buffers: the compiler can then prove that an
     // LDS-direct load into one does not alias the reads of another and leaves it in flight
-    __shared__ __attribute__((aligned(1024))) unsigned char xs0[kPM * kTileCols];
-    __shared__ __attribute__((aligned(1024))) unsigned char xs1[kPM * kTileCols];
-    __shared__ __attribute__((aligned(1024))) unsigned char xs2[kPM * kTileCols];
-    __shared__ __attribute__((aligned(1024))) unsigned char xs3[kPM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs0[PM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs1[PM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs2[PM * kTileCols];
+    __shared__ __attribute__((aligned(1024))) unsigned char xs3[PM * kTileCols];
     __shared__ float gs[kPN];                            // tanh(alpha) of the workgroup's rows
 
     const int tid = threadIdx.x, l = tid & 63, jl = l & 31, hf = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nb = blockIdx.x % p.NB, mb = blockIdx.x / p.NB;
+    const int nbg = blockIdx.x % p.NB, mb = blockIdx.x / p.NB;
+    int g = 0;
+    while (g + 1 < p.G && nbg >= p.L[g + 1].nb_start) ++g;
+    const PrefillLayer &L = p.L[g];
+    const int nb = nbg - L.nb_start;
     const int rb0 = nb * (kPN / kTileRows) + w * 2;      // this wavefront's first row-block
     const int m0 = mb * PM;
     const int mrows = min(PM, p.M - m0);
@@ -77,20 +90,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     rsrc_t wr[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        const bool ok = rb0 + rb < p.RBn;
-        wr[rb] = make_rsrc(p.packed + (size_t)(ok ? rb0 + rb : 0) * p.KT * 64, ok ? (unsigned)p.KT * kTileBytes : 0u);
+        const bool ok = rb0 + rb < L.RBn;
+        wr[rb] = make_rsrc(L.packed + (size_t)(ok ? rb0 + rb : 0) * p.KT * 64, ok ? (unsigned)p.KT * kTileBytes : 0u);
     }
     const rsrc_t xr = make_rsrc(p.xq + (size_t)m0 * p.Kp, (unsigned)mrows * p.Kp);
 
     {   // gate table
-        const rsrc_t ar = make_rsrc(p.alpha, p.rank > 0 ? (unsigned)p.N * 2u : 0u);
+        const rsrc_t ar = make_rsrc(L.alpha, L.rank > 0 ? (unsigned)L.N * 2u : 0u);
         const int n = nb * kPN + tid;
-        const float a = (float)half_bits(buf_load2(ar, (unsigned)n * 2u, n < p.N));
-        gs[tid] = p.rank > 0 ? tanhf(a) : 0.f;
+        const float a = (float)half_bits(buf_load2(ar, (unsigned)n * 2u, n < L.N));
+        gs[tid] = L.rank > 0 ? tanhf(a) : 0.f;
     }
 
     // the weight scale and the per-token scales of this lane's tokens, requested now, used in the epilogue
-    const float s_w = *p.s_w;
+    const float s_w = *L.s_w;
     float sx[kPG];
     int rs[kPG];
     {
@@ -132,42 +145,60 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 #pragma unroll
         for (int tg = 0; tg < kPG; ++tg) acc[rb][tg] = (v16i){};
 
-    auto compute = [&](const unsigned char *xbase, const v4u (&wuse)[2]) {   // the 32 MFMAs of one step
+    // One quarter of a step: the activation operands of 32 columns (piece pair t) for every
+    // token group, and the 2 x kPG MFMAs that use them.
+    auto reads = [&](const unsigned char *xbase, int t, v4i (&b)[kPG]) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            v4i b[kPG];
+        for (int tg = 0; tg < kPG; ++tg)
+            b[tg] = *reinterpret_cast<const v4i *>(xbase + xoff[t] + tg * 32 * kTileCols);
+    };
+    auto mfmas = [&](const v4u (&wuse)[2], int t, const v4i (&b)[kPG]) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const v4i a = widen_codes(wuse[rb][t]);
 #pragma unroll
             for (int tg = 0; tg < kPG; ++tg)
-                b[tg] = *reinterpret_cast<const v4i *>(xbase + xoff[t] + tg * 32 * kTileCols);
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                const v4i a = widen_codes(wuse[rb][t]);
-#pragma unroll
-                for (int tg = 0; tg < kPG; ++tg)
-                    acc[rb][tg] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[tg], acc[rb][tg], 0, 0, 0);
-            }
+                acc[rb][tg] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[tg], acc[rb][tg], 0, 0, 0);
         }
     };
 
-    // Software pipeline, three steps (3 x 128 columns) ahead.  Every step issues kLoads vector
-    // memory operations per wavefront (2 weight loads + kXP LDS-direct loads).  A step:
-    //   wait until this wavefront's loads of step kt have landed (the loads of steps kt+1 and
-    //   kt+2 may stay in flight); barrier: everyone's have, and everyone is done computing
-    //   step kt-1; request step kt+3 into the buffer step kt-1 used; compute step kt.
+    // Software pipeline.  Memory: four steps (4 x 128 columns) are in LDS or on their way; every
+    // step issues 2 + kXP vector memory operations per wavefront (2 weight loads, kXP LDS-direct
+    // loads).  Registers: the operands of a quarter are read from LDS while the MFMAs of the
+    // quarter before run, also across the step boundary -- the barrier that opens step kt+1
+    // stands before the last quarter of step kt:
+    //   quarters 0..2 of step kt (each: request the next quarter's operands, then the MFMAs);
+    //   wait until this wavefront's loads of step kt+1 have landed (those of steps kt+2 and
+    //   kt+3 may stay in flight) and its LDS reads of step kt have returned; barrier: everyone's
+    //   have; request quarter 0 of step kt+1; MFMAs of quarter 3; request step kt+4 into the
+    //   buffer and the weight registers step kt used.
     // The barrier is the bare instruction (the fence of __syncthreads would wait for all
     // loads in flight); the empty asm statements keep the compiler from moving memory
-    // operations across it.  Beyond the last step the descriptors return zeros, never used.
+    // operations across it, the scheduling barriers from sinking the LDS reads below the
+    // MFMAs that are to hide them.  Beyond the last step the descriptors return zeros, never used.
     constexpr int kLoads = 2 * (2 + kXP);            // two steps' worth may stay in flight
-    constexpr int kWaitTwoStepsInFlight = (kLoads & 0xF) | (7 << 4) | (15 << 8) | ((kLoads >> 4) << 14);
-#define HGF_STEP(XCUR, WCUR, XFILL, WFILL, KT)                    \
+    constexpr int kWaitTwoStepsInFlight = (kLoads & 0xF) | (7 << 4) | (0 << 8) | ((kLoads >> 4) << 14);
+    constexpr int kLoads3 = 3 * (2 + kXP);
+    constexpr int kWaitThreeStepsInFlight = (kLoads3 & 0xF) | (7 << 4) | (15 << 8) | ((kLoads3 >> 4) << 14);
+    v4i b0[kPG], b1[kPG];
+#define HGF_QUARTER(XREAD, TREAD, BREAD, WCUR, TUSE, BUSE)        \
     do {                                                          \
+        reads(XREAD, TREAD, BREAD);                               \
+        __builtin_amdgcn_sched_barrier(0);                        \
+        mfmas(WCUR, TUSE, BUSE);                                  \
+        __builtin_amdgcn_sched_barrier(0);                        \
+    } while (0)
+#define HGF_STEP(XCUR, WCUR, XNEXT, KT)                           \
+    do {                                                          \
+        HGF_QUARTER(XCUR, 1, b1, WCUR, 0, b0);                    \
+        HGF_QUARTER(XCUR, 2, b0, WCUR, 1, b1);                    \
+        HGF_QUARTER(XCUR, 3, b1, WCUR, 2, b0);                    \
         __builtin_amdgcn_s_waitcnt(kWaitTwoStepsInFlight);        \
         asm volatile("" ::: "memory");                            \
         __builtin_amdgcn_s_barrier();                             \
         asm volatile("" ::: "memory");                            \
-        stage(XFILL, WFILL, (KT) + 3);                            \
-        __builtin_amdgcn_sched_barrier(0);                        \
-        compute(XCUR, WCUR);                                      \
+        HGF_QUARTER(XNEXT, 0, b0, WCUR, 3, b1);                   \
+        stage(XCUR, WCUR, (KT) + 4);                              \
         __builtin_amdgcn_sched_barrier(0);                        \
     } while (0)
 
@@ -175,65 +206,77 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     stage(xs0, w0, 0);
     stage(xs1, w1, 1);
     stage(xs2, w2, 2);
+    stage(xs3, w3, 3);
+    __builtin_amdgcn_s_waitcnt(kWaitThreeStepsInFlight);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    reads(xs0, 0, b0);
+    __builtin_amdgcn_sched_barrier(0);
     int kt = 0;
     for (; kt + 3 < p.KT; kt += 4) {
-        HGF_STEP(xs0, w0, xs3, w3, kt);
-        HGF_STEP(xs1, w1, xs0, w0, kt + 1);
-        HGF_STEP(xs2, w2, xs1, w1, kt + 2);
-        HGF_STEP(xs3, w3, xs2, w2, kt + 3);
+        HGF_STEP(xs0, w0, xs1, kt);
+        HGF_STEP(xs1, w1, xs2, kt + 1);
+        HGF_STEP(xs2, w2, xs3, kt + 2);
+        HGF_STEP(xs3, w3, xs0, kt + 3);
     }
-    if (kt < p.KT) HGF_STEP(xs0, w0, xs3, w3, kt);
-    if (kt + 1 < p.KT) HGF_STEP(xs1, w1, xs0, w0, kt + 1);
-    if (kt + 2 < p.KT) HGF_STEP(xs2, w2, xs1, w1, kt + 2);
+    if (kt < p.KT) HGF_STEP(xs0, w0, xs1, kt);
+    if (kt + 1 < p.KT) HGF_STEP(xs1, w1, xs2, kt + 1);
+    if (kt + 2 < p.KT) HGF_STEP(xs2, w2, xs3, kt + 2);
 #undef HGF_STEP
+#undef HGF_QUARTER
     __syncthreads();                 // gs is complete; every wavefront is done with the activation buffers
 
     // ---- epilogue: correction up-projection on the f16 MFMA, gate, dequantise, store.
     //      Element 4*q + v of an accumulator is row 8*q + 4*hf + v of the row-block, for the
     //      token of the lane.
-    // SiLU(A x) of the tokens goes into the (now free) activation buffers, tokens 0..63
-    // into xs0 and 64..127 into xs1, rows of JS*32 bytes with the same XOR permutation of the
-    // 16-byte pieces; the B rows of both row-blocks go to registers.  All of it is requested
-    // in one burst: one memory round trip for the whole epilogue.
+    // SiLU(A x) of the tokens goes into the (now free) activation buffers: rows of JS*32
+    // bytes with the same XOR permutation of the 16-byte pieces, the image of all PM tokens
+    // cut into buffer-sized stretches (xs0 then xs1 for 128 tokens, xs0 then xs3 for 64);
+    // the B rows of both row-blocks go to registers.  All of it is requested in one burst:
+    // one memory round trip for the whole epilogue.
     constexpr int kRowBytes = JS * 32, kPieces = JS * 2, kMask = (kPieces < 8 ? kPieces : 8) - 1;
+    constexpr unsigned kBufBytes = PM * kTileCols;
+    auto hplace = [&](unsigned byte) -> unsigned char * {
+        return byte < kBufBytes ? xs0 + byte : (PM == 64 ? xs3 : xs1) + (byte - kBufBytes);
+    };
     v8h breg[2][JS > 0 ? JS : 1];
     if (JS > 0) {
-        const rsrc_t hr = make_rsrc(p.h16 + (size_t)m0 * p.hstride, (unsigned)mrows * p.hstride * 2u);
+        const rsrc_t hr = make_rsrc(L.h16 + (size_t)m0 * p.hstride, (unsigned)mrows * p.hstride * 2u);
 #pragma unroll
-        for (int buf = 0; buf < PM / 64; ++buf) {
-#pragma unroll
-            for (int i = 0; i < JS / 2; ++i) {
-                const unsigned byte = (unsigned)(4 * i + w) * 1024 + l * 16;
-                const unsigned row = byte / kRowBytes, slot = (byte % kRowBytes) / 16;
-                const unsigned piece = slot ^ (row & kMask);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(hr, (lds_ptr_t)((buf ? xs1 : xs0) + (4 * i + w) * 1024), 16,
-                                                         (int)((buf * 64 + row) * (unsigned)p.hstride * 2u + piece * 16), 0, 0, 0);
-            }
+        for (int i = 0; i < PM * kRowBytes / 4096; ++i) {    // 4 KiB per instruction of the four wavefronts
+            const unsigned byte = (unsigned)(4 * i + w) * 1024 + l * 16;
+            const unsigned row = byte / kRowBytes, slot = (byte % kRowBytes) / 16;
+            const unsigned piece = slot ^ (row & kMask);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(hr, (lds_ptr_t)hplace((unsigned)(4 * i + w) * 1024), 16,
+                                                     (int)(row * (unsigned)p.hstride * 2u + piece * 16), 0, 0, 0);
         }
-        const rsrc_t br = make_rsrc(p.B, (unsigned)p.N * p.rank * 2u);
-        const bool bvec = (p.rank % 8) == 0;
+        const int rank = L.rank;
+        const rsrc_t br = make_rsrc(L.B, (unsigned)L.N * rank * 2u);
+        const bool bvec = (rank % 8) == 0;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             const int brow = (rb0 + rb) * kTileRows + jl;
 #pragma unroll
             for (int js = 0; js < JS; ++js) {
                 const int j0 = js * 16 + hf * 8;
-                breg[rb][js] = bvec ? buf_load8h<true>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N)
-                                    : buf_load8h<false>(br, (unsigned)brow * p.rank + j0, p.rank - j0, brow < p.N);
+                breg[rb][js] = bvec ? buf_load8h<true>(br, (unsigned)brow * rank + j0, rank - j0, brow < L.N)
+                                    : buf_load8h<false>(br, (unsigned)brow * rank + j0, rank - j0, brow < L.N);
             }
         }
         __syncthreads();             // waits for the loads above and makes the staged rows visible
     }
-    const bool nvec = (p.N % 4) == 0;
+    const int N = L.N;
+    _Float16 *const y = L.y;
+    const bool nvec = (N % 4) == 0;
     const int nw0 = rb0 * kTileRows;                 // first of this wavefront's 64 output rows
     // Coalesced store path: a token's 64 outputs of this wavefront are 128 contiguous bytes of
     // y.  The fp16 results of 32 tokens at a time are transposed through a wavefront-private
-    // LDS patch (rows of 144 bytes: the 16 spare bytes spread the banks) and leave as 16-byte
-    // stores, eight lanes per token.  Needs the whole 64-row strip in range and 16-byte
+    // LDS patch (32 rows of 128 bytes, 16-byte pieces permuted like the activation tile's) and
+    // leave as 16-byte stores, eight lanes per token.  Needs the whole 64-row strip in range and 16-byte
     // aligned rows of y; otherwise (ragged d_out, or the int32 debug output) direct stores.
-    const bool wide = (p.N % 8) == 0 && nw0 + 64 <= p.N && p.acc_debug == nullptr;
-    unsigned char *patch = (w < 2 ? xs2 : xs3) + (w & 1) * 8192;
-    constexpr int kPatchStride = 144;
+    const bool wide = (N % 8) == 0 && nw0 + 64 <= N && p.acc_debug == nullptr;
+    unsigned char *patch = (PM == 64 ? (w < 2 ? xs1 : xs2) : (w < 2 ? xs2 : xs3)) + (w & 1) * 4096;
 
 #pragma unroll
     for (int tg = 0; tg < kPG; ++tg) {
@@ -241,8 +284,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
         const float scale = sx[tg] * s_w;
         v16f corr[2] = {(v16f){}, (v16f){}};
         if (JS > 0) {
-            const unsigned row = (unsigned)(tg & 1) * 32 + jl;
-            const unsigned char *hrow = ((tg >> 1) ? xs1 : xs0) + row * kRowBytes;
+            const unsigned row = (unsigned)tg * 32 + jl;
+            const unsigned char *hrow = hplace((unsigned)tg * 32 * kRowBytes) + jl * kRowBytes;
 #pragma unroll
             for (int js = 0; js < JS; ++js) {
                 const unsigned piece = (unsigned)(js * 2 + hf) ^ (row & kMask);
@@ -267,17 +310,17 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
                     o[v] = (_Float16)((float)a[v] * scale + gs[(w * 2 + rb) * kTileRows + r0 + v] * corr[rb][4 * q + v]);
                 }
                 if (wide) {
-                    *reinterpret_cast<v4h *>(patch + jl * kPatchStride + (rb * kTileRows + r0) * 2) = o;
+                    *reinterpret_cast<v4h *>(patch + jl * kTileCols + piece_slot(rb * 4 + q, jl) * 16 + hf * 8) = o;
                 } else if (m < p.M) {
-                    const size_t at = (size_t)m * p.N + nl;
-                    if (nvec && nl + 3 < p.N) {
-                        *reinterpret_cast<v4h *>(p.y + at) = o;
+                    const size_t at = (size_t)m * N + nl;
+                    if (nvec && nl + 3 < N) {
+                        *reinterpret_cast<v4h *>(y + at) = o;
                         if (p.acc_debug) *reinterpret_cast<v4i *>(p.acc_debug + at) = (v4i){a[0], a[1], a[2], a[3]};
                     } else {
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            if (nl + v < p.N) {
-                                p.y[at + v] = o[v];
+                            if (nl + v < N) {
+                                y[at + v] = o[v];
                                 if (p.acc_debug) p.acc_debug[at + v] = a[v];
                             }
                         }
@@ -291,9 +334,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int tok = i * 8 + (l >> 3), piece = l & 7;
-                const v4u v = *reinterpret_cast<const v4u *>(patch + tok * kPatchStride + piece * 16);
+                const v4u v = *reinterpret_cast<const v4u *>(patch + tok * kTileCols + piece_slot(piece, tok) * 16);
                 const int mm = m0 + tg * 32 + tok;
-                if (mm < p.M) *reinterpret_cast<v4u *>(p.y + (size_t)mm * p.N + nw0 + piece * 8) = v;
+                if (mm < p.M) *reinterpret_cast<v4u *>(y + (size_t)mm * N + nw0 + piece * 8) = v;
             }
         }
     }
@@ -301,28 +344,11 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 
 }  // namespace
 
-hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const hgf_layer &L, _Float16 *y,
-                          int32_t *acc_debug, hipStream_t st)
+// Layers [0, G) read the same quantised activations (the workspace's); consecutive layers whose
+// correction paths have the same padded rank share a launch.
+hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
+                          void *const *ys, int32_t *acc_debug, hipStream_t st)
 {
-    PrefillParams p;
-    p.packed = reinterpret_cast<const v4u *>(L.W_packed);
-    p.xq = ws.xq;
-    p.s_x = ws.s_x;
-    p.rowsum = ws.rowsum;
-    p.s_w = L.s_w;
-    p.B = reinterpret_cast<const _Float16 *>(L.B_f16);
-    p.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-    p.h16 = h16;
-    p.y = y;
-    p.acc_debug = acc_debug;
-    p.M = M;
-    p.N = L.d_out;
-    p.Kp = round_up(L.d_in, kTileCols);
-    p.KT = p.Kp / kTileCols;
-    p.RBn = round_up(L.d_out, kTileRows) / kTileRows;
-    p.rank = L.rank;
-    p.hstride = h_stride(L.rank > 0 ? L.rank : 1);
-    p.NB = (L.d_out + kPN - 1) / kPN;
     static int num_cus = 0;
     if (num_cus == 0) {
         int dev = 0, n = 0;
@@ -333,24 +359,65 @@ hipError_t launch_prefill(const Workspace &ws, const _Float16 *h16, int M, const
         }
         num_cus = n;
     }
-    // fewer 256 x 128 tiles than two per compute unit: 256 x 64 tiles, twice as many workgroups
-    const bool narrow = p.NB * ((M + kPM - 1) / kPM) < 2 * num_cus;
-    const int pm = narrow ? 64 : kPM;
-    const int MB = (M + pm - 1) / pm;
-    const dim3 grid(p.NB * MB), block(256);
+    auto steps_of = [](const hgf_layer &L) { return L.rank > 0 ? h_stride(L.rank) / 16 : 0; };
+    for (int first = 0; first < G;) {
+        int n = 1;
+        while (!acc_debug && first + n < G && steps_of(layers[first + n]) == steps_of(layers[first])) ++n;
+        PrefillParams p;
+        p.xq = ws.xq;
+        p.s_x = ws.s_x;
+        p.rowsum = ws.rowsum;
+        p.acc_debug = acc_debug;
+        p.M = M;
+        p.Kp = round_up(layers[first].d_in, kTileCols);
+        p.KT = p.Kp / kTileCols;
+        p.hstride = h_stride(layers[first].rank > 0 ? layers[first].rank : 1);
+        p.G = n;
+        p.NB = 0;
+        for (int g = 0; g < n; ++g) {
+            const hgf_layer &L = layers[first + g];
+            PrefillLayer &P = p.L[g];
+            P.packed = reinterpret_cast<const v4u *>(L.W_packed);
+            P.s_w = L.s_w;
+            P.B = reinterpret_cast<const _Float16 *>(L.B_f16);
+            P.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
+            P.h16 = h16[first + g];
+            P.y = reinterpret_cast<_Float16 *>(ys[first + g]);
+            P.N = L.d_out;
+            P.RBn = round_up(L.d_out, kTileRows) / kTileRows;
+            P.rank = L.rank;
+            P.nb_start = p.NB;
+            p.NB += (L.d_out + kPN - 1) / kPN;
+        }
+        for (int g = n; g < kMaxGroup; ++g) p.L[g] = p.L[0];
+        // Tile width.  Two workgroups fit a compute unit, so the tiles run in rounds of
+        // 2 x num_cus; a round of 256 x 64 tiles costs a little over half a round of 256 x 128
+        // tiles (each widened weight operand feeds two MFMAs instead of four).  Take the width
+        // whose whole rounds cost less: the wide tile unless its last round would be mostly empty.
+        const int slots = 2 * num_cus;
+        const int rounds_wide = (p.NB * ((M + kPM - 1) / kPM) + slots - 1) / slots;
+        const int rounds_narrow = (p.NB * ((M + 63) / 64) + slots - 1) / slots;
+        const bool narrow = rounds_narrow * 21 < rounds_wide * 40;
+        const int pm = narrow ? 64 : kPM;
+        const int MB = (M + pm - 1) / pm;
+        const dim3 grid(p.NB * MB), block(256);
 #define HGF_PREFILL(JS)                                                                        \
     do {                                                                                       \
         if (narrow) hipLaunchKernelGGL((prefill_kernel<JS, 64>), grid, block, 0, st, p);       \
         else hipLaunchKernelGGL((prefill_kernel<JS, 128>), grid, block, 0, st, p);             \
     } while (0)
-    switch (L.rank > 0 ? p.hstride / 16 : 0) {
-        case 0: HGF_PREFILL(0); break;
-        case 2: HGF_PREFILL(2); break;
-        case 4: HGF_PREFILL(4); break;
-        default: HGF_PREFILL(8); break;
-    }
+        switch (steps_of(layers[first])) {
+            case 0: HGF_PREFILL(0); break;
+            case 2: HGF_PREFILL(2); break;
+            case 4: HGF_PREFILL(4); break;
+            default: HGF_PREFILL(8); break;
+        }
 #undef HGF_PREFILL
-    return hipGetLastError();
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        first += n;
+    }
+    return hipSuccess;
 }
 
 }  // namespace hgf
