@@ -182,15 +182,14 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     return from_hip(launch_decode(dp, K, st));
 }
 
-// Large M: per group of layers that read the same activations, one quantiser launch, one
-// launch of the down-projections with SiLU (all layers), then one launch of the int8 MFMA
-// prefill kernel over the tiles of all layers.
+// Large M: per group of layers that read the same activations, one launch for the quantiser
+// and the down-projections with SiLU of all layers (both read x), then one launch of the int8
+// MFMA prefill kernel over the tiles of all layers.
 hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
                            int32_t *acc_debug, const Workspace &ws, hipStream_t st)
 {
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(x);
     const int K = layers[0].d_in;
-    if (launch_quantize(xh, M, K, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess) return HGF_ERR_DEVICE;
     const _Float16 *A[kMaxGroup];
     _Float16 *h16[kMaxGroup];
     int rank[kMaxGroup];
@@ -199,7 +198,7 @@ hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G,
         rank[g] = layers[g].rank;
         h16[g] = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
     }
-    if (launch_corr_down(xh, M, K, G, A, rank, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
+    if (launch_corr_down(xh, M, K, G, A, rank, h16, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess) return HGF_ERR_DEVICE;
     ProfileScope prof(1, st);
     return from_hip(launch_prefill(ws, h16, M, layers, G, ys, acc_debug, st));
 }

@@ -41,8 +41,9 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 __device__ inline unsigned slot_of(unsigned piece, unsigned row) { return piece ^ (row & 15u); }
 
 // RT: rank tiles of 32 covering the padded row of h16 (1, 2 or 4).  KC: columns per stretch.
+// (bx, by): token tile and rank tile of the workgroup.
 template <int RT, int KC>
-__global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
+__device__ inline void corr_down_tile(const CorrParams &p, const int bx, const int by)
 {
     constexpr int kRowB = KC * 2;               // bytes per staged row
     constexpr int kPieces = kRowB / 16;         // 16-byte pieces per row = lanes per row of an LDS-direct load
@@ -56,14 +57,14 @@ __global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
 
     const int tid = threadIdx.x, l = tid & 63, jl = l & 31, hf = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m0 = blockIdx.x * 32;
+    const int m0 = bx * 32;
     const int mrows = min(32, p.M - m0);
     // this workgroup's layer and first rank (RT tiles of 32 from there)
     int g = 0;
 #pragma unroll
     for (int i = 1; i < kMaxGroup; ++i)
-        if (i < p.G && (int)blockIdx.y >= p.tile_start[i]) g = i;
-    const int j_first = ((int)blockIdx.y - p.tile_start[g]) * 32 * RT;
+        if (i < p.G && by >= p.tile_start[i]) g = i;
+    const int j_first = (by - p.tile_start[g]) * 32 * RT;
     const int rank = p.rank4[g], hstride = p.hstride4[g];
     _Float16 *const h16 = p.h4[g];
     const int arows = min(RT * 32, rank - j_first);          // rows of A this workgroup reads (may be <= 0)
@@ -177,6 +178,78 @@ __global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
     }
 }
 
+template <int RT, int KC>
+__global__ __launch_bounds__(256) void corr_down_kernel(CorrParams p)
+{
+    corr_down_tile<RT, KC>(p, blockIdx.x, blockIdx.y);
+}
+
+// The activation quantiser (Sec. 2.2.1 of the HGF paper; Algorithm 1, steps 1-2; the arithmetic
+// of quantize_kernel, bit for bit) with one wavefront per token: the row stays in registers
+// between the absmax pass and the rounding pass (NV 16-byte pieces per lane: d_in <= 512 NV),
+// so x is read once and nothing goes through LDS.
+struct QuantParams {
+    const _Float16 *x;
+    int8_t *xq;
+    float *s_x;
+    int32_t *rowsum;
+    int M, K, Kp;
+};
+
+template <int NV>
+__device__ inline void quantize_row(const QuantParams &q, const int m, const int l)
+{
+    if (m >= q.M) return;
+    const rsrc_t xr = make_rsrc(q.x + (size_t)m * q.K, (unsigned)q.K * 2u);
+    v4u raw[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) raw[i] = buf_load16(xr, (unsigned)(i * 64 + l) * 16u);   // beyond the row: zeros
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const v8h v = __builtin_bit_cast(v8h, raw[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf((float)v[j]));
+    }
+    amax = fmaxf(wave_max(amax), 1e-5f);
+    const float inv = 127.0f / amax;
+    int sum = 0;
+    uint2 *out8 = reinterpret_cast<uint2 *>(q.xq + (size_t)m * q.Kp);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const v8h v = __builtin_bit_cast(v8h, raw[i]);
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int c = quant1((float)v[j], inv);
+            sum += c;
+            w[j >> 2] |= (uint32_t)(c & 0xff) << (8 * (j & 3));
+        }
+        if ((i * 64 + l) * 8 < q.Kp) out8[i * 64 + l] = make_uint2(w[0], w[1]);
+    }
+    sum = wave_sum(sum);
+    if (l == 0) {
+        q.s_x[m] = amax / 127.0f;
+        if (q.rowsum) q.rowsum[m] = sum;
+    }
+}
+
+// Both halves of the preparation of a group of prefill layers in one launch: the first
+// `ncorr` workgroups are the down-projection tiles (few, long: a dozen dependent memory
+// round trips each), the rest quantise four tokens each (many, short) and fill the compute
+// units the tiles leave idle.  Both only read x.
+template <int NV>
+__global__ __launch_bounds__(256) void prepare_kernel(CorrParams p, QuantParams q, int ncorr, int token_tiles)
+{
+    const int b = blockIdx.x;
+    if (b < ncorr) {
+        corr_down_tile<1, 256>(p, b % token_tiles, b / token_tiles);
+    } else {
+        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        quantize_row<NV>(q, (b - ncorr) * 4 + w, threadIdx.x & 63);
+    }
+}
+
 // d_in % 8 != 0 (rows not 16-byte aligned): one thread per (token, rank) pair with plain
 // loads.  Slow and simple, for odd shapes only.
 __global__ __launch_bounds__(256) void corr_down_ragged_kernel(CorrParams p)
@@ -196,8 +269,10 @@ __global__ __launch_bounds__(256) void corr_down_ragged_kernel(CorrParams p)
 }  // namespace
 
 // Layers 0..G-1 read the same x; layer g's result goes to h16[g] ([M, h_stride(rank[g])] fp16).
+// With xq != nullptr the quantised activations, their scales and sums are produced as well --
+// in the same launch where the shapes allow it, by launch_quantize before otherwise.
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
-                            _Float16 *const *h16, hipStream_t st)
+                            _Float16 *const *h16, int8_t *xq, float *s_x, int32_t *rowsum, hipStream_t st)
 {
     CorrParams p;
     p.x = x;
@@ -205,6 +280,11 @@ hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float
     p.K = K;
     bool vec = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
     for (int g = 0; g < G; ++g) vec = vec && (rank[g] == 0 || reinterpret_cast<uintptr_t>(A[g]) % 16 == 0);
+    const bool together = vec && xq != nullptr && K <= 512 * 32;
+    if (xq != nullptr && !together) {
+        const hipError_t e = launch_quantize(x, M, K, xq, s_x, rowsum, st);
+        if (e != hipSuccess) return e;
+    }
     if (!vec) {
         for (int g = 0; g < G; ++g) {
             if (rank[g] == 0) continue;
@@ -228,9 +308,27 @@ hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float
         if (g < G && rank[g] > 0) tiles += p.hstride4[g] / 32;     // tiles cover the padded row: every column is written
     }
     p.tile_start[kMaxGroup] = tiles;
-    if (tiles == 0) return hipSuccess;
     p.steps = (K + 255) / 256;
-    hipLaunchKernelGGL((corr_down_kernel<1, 256>), dim3((M + 31) / 32, tiles), dim3(256), 0, st, p);
+    const int token_tiles = (M + 31) / 32;
+    if (together) {
+        QuantParams q;
+        q.x = x;
+        q.xq = xq;
+        q.s_x = s_x;
+        q.rowsum = rowsum;
+        q.M = M;
+        q.K = K;
+        q.Kp = round_up(K, kTileCols);
+        const int ncorr = token_tiles * tiles;
+        const dim3 grid(ncorr + (M + 3) / 4), block(256);
+        const int pieces = (q.Kp + 511) / 512;
+        if (pieces <= 8) hipLaunchKernelGGL(prepare_kernel<8>, grid, block, 0, st, p, q, ncorr, token_tiles);
+        else if (pieces <= 16) hipLaunchKernelGGL(prepare_kernel<16>, grid, block, 0, st, p, q, ncorr, token_tiles);
+        else hipLaunchKernelGGL(prepare_kernel<32>, grid, block, 0, st, p, q, ncorr, token_tiles);
+        return hipGetLastError();
+    }
+    if (tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL((corr_down_kernel<1, 256>), dim3(token_tiles, tiles), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

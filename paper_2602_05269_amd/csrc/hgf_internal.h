@@ -258,7 +258,7 @@ hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st);
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st);
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
-                            _Float16 *const *h16, hipStream_t st);
+                            _Float16 *const *h16, int8_t *xq, float *s_x, int32_t *rowsum, hipStream_t st);
 int prologue_slices(int M, int K);
 hipError_t launch_prologue(ProParams &p, _Float16 *const *h16, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
