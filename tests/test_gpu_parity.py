@@ -116,6 +116,47 @@ def test_large_m_parity(M, K, N, r, ws):
     g.check_forward(c["x"])
 
 
+@pytest.mark.parametrize("M,K,N,r", [(70, 4104, 96, 8), (66, 8200, 64, 16), (65, 16392, 40, 8)])
+def test_large_m_long_rows_parity(M, K, N, r, ws):
+    """Rows of 4104, 8200 and 16392 columns: the prefill path's quantiser keeps 16 and 32
+    register pieces per lane for the first two (and shares the down-projections' launch);
+    the third is beyond that and takes the quantiser's own launch."""
+    c = synth.make_custom(2100 + M + K + N + r, M, K, N, r, act="student_t4")
+    g = GpuLayer(c, ws if K <= 11008 else hb.Workspace(M, K, 64, 128))
+    g.check_forward(c["x"])
+
+
+def test_prefill_group_shares_one_launch(ws):
+    """Four layers read slot 0 at M = 150: ranks 16, 24 and 32 pad to the same 32 columns of
+    SiLU(A x), so their tiles (d_out 300, 256 and 40: two, one and one row tiles, the first and
+    last ragged) go out as one launch of the prefill kernel; the rank-64 layer takes its own.
+    Each output is checked against the oracle and must equal, bit for bit, what the same layer
+    gives on its own."""
+    M, K = 150, 384
+    shapes = [(300, 16), (256, 24), (40, 32), (128, 64)]
+    cases, layers = [], []
+    slots = [None] * (len(shapes) + 1)
+    for i, (N, r) in enumerate(shapes):
+        c = synth.make_custom(7700 + i, M, K, N, r, act="student_t4", lora_std=0.05, w_std=0.05)
+        if i == 0:
+            x = c["x"]
+            slots[0] = dev(x)
+        g = GpuLayer(c, ws)
+        g.layer.c.src_slot, g.layer.c.dst_slot = 0, i + 1
+        cases.append(g)
+        layers.append(g.layer)
+        slots[i + 1] = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    hb.hgf_stack_forward(hb.Stack(layers, slots, M), ws)
+    torch.cuda.synchronize()
+    for i, g in enumerate(cases):
+        got = slots[i + 1].cpu().numpy()
+        ref = g.oracle(x)
+        assert_close_fp16(got, ref["y"], f"layer {i}")
+        y1, acc1 = g.forward(x)
+        assert np.array_equal(acc1, ref["acc"])
+        assert np.array_equal(got, y1), f"layer {i}: grouped launch and single layer differ"
+
+
 def test_gate_off_and_rank0_are_the_pure_ternary_layer(ws):
     c = synth.make_custom(77, 8, 512, 256, 32)
     full = GpuLayer(c, ws)
