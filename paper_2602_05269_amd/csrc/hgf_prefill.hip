@@ -125,14 +125,18 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
         const unsigned row = (unsigned)(4 * i + w) * 8 + (l >> 3);
         xsrc[i] = row * p.Kp + piece_slot(l & 7, row) * 16;
     }
+    // The step enters the addresses as a scalar offset (no vector arithmetic per request); a
+    // request beyond the last step repeats the last step's (in bounds, never used).
+    const int kt_last = p.KT - 1;
     auto stage = [&](unsigned char *buf, v4u (&wfill)[2], int kt) {   // request step kt
-        const bool ok = kt < p.KT;
+        const int ks = min(kt, kt_last);
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) wfill[rb] = buf_load16(wr[rb], (unsigned)kt * kTileBytes + l * 16);
+        for (int rb = 0; rb < 2; ++rb)
+            wfill[rb] = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(wr[rb], l * 16, ks * kTileBytes, 0));
 #pragma unroll
         for (int i = 0; i < kXP; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)(buf + (4 * i + w) * 1024), 16,
-                                                     (int)(ok ? xsrc[i] + (unsigned)kt * kTileCols : kOob), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)(buf + (4 * i + w) * 1024), 16, (int)xsrc[i],
+                                                     ks * kTileCols, 0, 0);
     };
     // Activation reads: lane (jl, hf) reads piece 2*t + hf of rows 32*tg + jl
     unsigned xoff[4];
@@ -152,26 +156,30 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
         for (int tg = 0; tg < kPG; ++tg)
             b[tg] = *reinterpret_cast<const v4i *>(xbase + xoff[t] + tg * 32 * kTileCols);
     };
-    auto mfmas = [&](const v4u (&wuse)[2], int t, const v4i (&b)[kPG]) {
+    auto widen = [&](const v4u (&wuse)[2], int t, v4i (&a)[2]) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const v4i a = widen_codes(wuse[rb][t]);
+        for (int rb = 0; rb < 2; ++rb) a[rb] = widen_codes(wuse[rb][t]);
+    };
+    auto mfmas = [&](const v4i (&a)[2], const v4i (&b)[kPG]) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int tg = 0; tg < kPG; ++tg)
-                acc[rb][tg] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[tg], acc[rb][tg], 0, 0, 0);
-        }
+                acc[rb][tg] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[rb], b[tg], acc[rb][tg], 0, 0, 0);
     };
 
     // Software pipeline.  Memory: four steps (4 x 128 columns) are in LDS or on their way; every
     // step issues 2 + kXP vector memory operations per wavefront (2 weight loads, kXP LDS-direct
-    // loads).  Registers: the operands of a quarter are read from LDS while the MFMAs of the
-    // quarter before run, also across the step boundary -- the barrier that opens step kt+1
-    // stands before the last quarter of step kt:
+    // loads).  Registers: the operands of a quarter are read from LDS and its weight codes widened
+    // while the MFMAs of the quarter before run -- the instructions are dealt out between the
+    // MFMAs (one MFMA, two vector instructions, every other time an LDS read), so that they issue
+    // while the matrix core is busy with the MFMA before them -- also across the step boundary:
+    // the barrier that opens step kt+1 stands before the last quarter of step kt:
     //   quarters 0..2 of step kt (each: request the next quarter's operands, then the MFMAs);
     //   wait until this wavefront's loads of step kt+1 have landed (those of steps kt+2 and
     //   kt+3 may stay in flight) and its LDS reads of step kt have returned; barrier: everyone's
-    //   have; request quarter 0 of step kt+1; MFMAs of quarter 3; request step kt+4 into the
-    //   buffer and the weight registers step kt used.
+    //   have; request quarter 0 of step kt+1 and, from memory, step kt+4 into the buffer and the
+    //   weight registers step kt used, between the MFMAs of quarter 3.
     // The barrier is the bare instruction (the fence of __syncthreads would wait for all
     // loads in flight); the empty asm statements keep the compiler from moving memory
     // operations across it, the scheduling barriers from sinking the LDS reads below the
@@ -180,25 +188,39 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     constexpr int kWaitTwoStepsInFlight = (kLoads & 0xF) | (7 << 4) | (0 << 8) | ((kLoads >> 4) << 14);
     constexpr int kLoads3 = 3 * (2 + kXP);
     constexpr int kWaitThreeStepsInFlight = (kLoads3 & 0xF) | (7 << 4) | (15 << 8) | ((kLoads3 >> 4) << 14);
-    v4i b0[kPG], b1[kPG];
-#define HGF_QUARTER(XREAD, TREAD, BREAD, WCUR, TUSE, BUSE)        \
+    v4i b0[kPG], b1[kPG], a0[2], a1[2];
+    constexpr int kMfma = 0x008, kValu = 0x002, kLdsRead = 0x100, kVmemRead = 0x020;    // instruction classes of the scheduler hints
+#define HGF_QUARTER(XREAD, WREAD, TREAD, BREAD, AREAD, AUSE, BUSE)        \
     do {                                                          \
         reads(XREAD, TREAD, BREAD);                               \
-        __builtin_amdgcn_sched_barrier(0);                        \
-        mfmas(WCUR, TUSE, BUSE);                                  \
+        widen(WREAD, TREAD, AREAD);                               \
+        mfmas(AUSE, BUSE);                                        \
+        _Pragma("unroll") for (int i_ = 0; i_ < 2 * kPG; ++i_) {  \
+            __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);    \
+            __builtin_amdgcn_sched_group_barrier(kValu, 2, 0);    \
+            if (i_ % 2 == 0) __builtin_amdgcn_sched_group_barrier(kLdsRead, 1, 0); \
+        }                                                         \
         __builtin_amdgcn_sched_barrier(0);                        \
     } while (0)
-#define HGF_STEP(XCUR, WCUR, XNEXT, KT)                           \
+#define HGF_STEP(XCUR, WCUR, XNEXT, WNEXT, KT)                    \
     do {                                                          \
-        HGF_QUARTER(XCUR, 1, b1, WCUR, 0, b0);                    \
-        HGF_QUARTER(XCUR, 2, b0, WCUR, 1, b1);                    \
-        HGF_QUARTER(XCUR, 3, b1, WCUR, 2, b0);                    \
+        HGF_QUARTER(XCUR, WCUR, 1, b1, a1, a0, b0);               \
+        HGF_QUARTER(XCUR, WCUR, 2, b0, a0, a1, b1);               \
+        HGF_QUARTER(XCUR, WCUR, 3, b1, a1, a0, b0);               \
         __builtin_amdgcn_s_waitcnt(kWaitTwoStepsInFlight);        \
         asm volatile("" ::: "memory");                            \
         __builtin_amdgcn_s_barrier();                             \
         asm volatile("" ::: "memory");                            \
-        HGF_QUARTER(XNEXT, 0, b0, WCUR, 3, b1);                   \
+        reads(XNEXT, 0, b0);                                      \
+        widen(WNEXT, 0, a0);                                      \
+        mfmas(a1, b1);                                            \
         stage(XCUR, WCUR, (KT) + 4);                              \
+        _Pragma("unroll") for (int i_ = 0; i_ < 2 * kPG; ++i_) {  \
+            __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);    \
+            __builtin_amdgcn_sched_group_barrier(kValu, 2, 0);    \
+            if (i_ % 2 == 0) __builtin_amdgcn_sched_group_barrier(kLdsRead, 1, 0); \
+            else __builtin_amdgcn_sched_group_barrier(kVmemRead, 2, 0); \
+        }                                                         \
         __builtin_amdgcn_sched_barrier(0);                        \
     } while (0)
 
@@ -212,17 +234,18 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     reads(xs0, 0, b0);
+    widen(w0, 0, a0);
     __builtin_amdgcn_sched_barrier(0);
     int kt = 0;
     for (; kt + 3 < p.KT; kt += 4) {
-        HGF_STEP(xs0, w0, xs1, kt);
-        HGF_STEP(xs1, w1, xs2, kt + 1);
-        HGF_STEP(xs2, w2, xs3, kt + 2);
-        HGF_STEP(xs3, w3, xs0, kt + 3);
+        HGF_STEP(xs0, w0, xs1, w1, kt);
+        HGF_STEP(xs1, w1, xs2, w2, kt + 1);
+        HGF_STEP(xs2, w2, xs3, w3, kt + 2);
+        HGF_STEP(xs3, w3, xs0, w0, kt + 3);
     }
-    if (kt < p.KT) HGF_STEP(xs0, w0, xs1, kt);
-    if (kt + 1 < p.KT) HGF_STEP(xs1, w1, xs2, kt + 1);
-    if (kt + 2 < p.KT) HGF_STEP(xs2, w2, xs3, kt + 2);
+    if (kt < p.KT) HGF_STEP(xs0, w0, xs1, w1, kt);
+    if (kt + 1 < p.KT) HGF_STEP(xs1, w1, xs2, w2, kt + 1);
+    if (kt + 2 < p.KT) HGF_STEP(xs2, w2, xs3, w3, kt + 2);
 #undef HGF_STEP
 #undef HGF_QUARTER
     __syncthreads();                 // gs is complete; every wavefront is done with the activation buffers
