@@ -134,7 +134,7 @@ typedef struct {
  *   acc_debug int32 [M, d_out] or NULL: receives the exact integer accumulators
  *             sum_k T[n,k] x_q[m,k] of step 3 (for parity tests)
  *
- * M <= 64 runs the bandwidth-bound decode kernel (weights streamed once); larger M
+ * M <= 40 runs the bandwidth-bound decode kernels (weights streamed once); larger M
  * runs the int8 MFMA prefill kernel.  Both give the same integers. */
 hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void *y_f16,
                               int32_t *acc_debug, void *workspace, size_t workspace_bytes,
@@ -170,7 +170,7 @@ void hgf_set_decode_target_workgroups(int n);
  * d_in <= 12288.  level 2 (default): hgf_stack_forward runs whole runs of groups of layers as
  * one persistent launch (activations handed from layer to layer inside the launch), and
  * single groups as level 1; level 1: each group of layers is one persistent launch;
- * level 0: the two-launch path that serves 5..64 tokens.  Results agree bit for bit in the
+ * level 0: the two-launch path that serves 5..40 tokens.  Results agree bit for bit in the
  * integers; the fp16 outputs may differ in the last place (different split of A x). */
 void hgf_set_single_launch(int level);
 

@@ -99,7 +99,7 @@ struct ProfileScope {
     }
 };
 
-// Decode (M <= 64): `G` layers that read the same activations `x` run as two launches:
+// Decode (M <= kMaxDecodeM): `G` layers that read the same activations `x` run as two launches:
 // the fused prologue (quantiser + partial sums of every A x) and one grouped main kernel.
 hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
                             int32_t *acc_debug, const Workspace &ws, hipStream_t st)

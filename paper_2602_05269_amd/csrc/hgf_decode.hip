@@ -1,4 +1,4 @@
-// Decode kernel (M <= 64): packed ternary weights x int8 activations, fused with
+// Decode kernel (up to 64 tokens; the library routes up to 40 here): packed ternary weights x int8 activations, fused with
 // dequantisation, the rank-r up-projection and the gate.
 //
 // Algorithm 1 of the HGF paper, steps 3, 4, 7 and 8:
