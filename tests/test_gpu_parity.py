@@ -73,7 +73,7 @@ def test_config0_full_parity(ws):
 @pytest.mark.parametrize("M,K,N,r", [
     (1, 64, 64, 16), (1, 512, 512, 32), (2, 100, 37, 8), (4, 1365, 130, 32), (8, 256, 192, 1),
     (16, 2048, 256, 64), (17, 320, 257, 24), (33, 1000, 66, 128), (48, 4096, 128, 48), (64, 704, 320, 128),
-    (1, 11008, 256, 128), (5, 63, 1, 5),
+    (1, 11008, 256, 128), (5, 63, 1, 5), (40, 768, 200, 64), (41, 768, 200, 64),
 ])
 def test_decode_shapes_parity(M, K, N, r, ws):
     c = synth.make_custom(1000 + M + K + N + r, M, K, N, r, act="student_t3")
