@@ -17,6 +17,9 @@ M=2048).
 
 `--copy-probe MIB` instead runs a plain elementwise copy of that many MiB a few times:
 the kernel of known size against which the HBM counters are scaled.
+`--mfma-probe` instead prints what a loop of nothing but the prefill kernel's MFMA sustains
+on constant, ternary-code x random and random operands (the chip's clock gives way under the
+matrix cores' power): the practical ceiling beside the published int8 peak.
 """
 from __future__ import annotations
 
@@ -152,6 +155,19 @@ def recorded_traffic():
     return None
 
 
+def mfma_probe() -> int:
+    """The yardstick beside the published int8 peak: what the matrix cores sustain on this
+    layer's kind of operands once the chip has settled its clock under their power."""
+    torch.cuda.set_device(0)
+    out = {"probe": "v_mfma_i32_32x32x32_i8 only, 8 accumulators, 2 workgroups x 4 wavefronts per compute unit",
+           "published_peak_TOPS": INT8_PEAK_TOPS}
+    for kind, name in ((0, "constant"), (1, "codes_0_2_x_random_int8"), (2, "random_int8")):
+        tops, ghz = hb.hgf_probe_mfma_rate(kind, 800)
+        out[name] = {"TOPS": round(tops, 1), "clock_GHz": round(ghz, 3)}
+    print(json.dumps(out))
+    return 0
+
+
 def copy_probe(mib: int) -> int:
     """A plain copy of `mib` MiB (read once, written once) by an elementwise kernel, five times."""
     n = mib * (1 << 20) // 4
@@ -206,6 +222,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--target-wgs", type=int, default=0, help="decode workgroups per launch (0 = library default)")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="print the int8 rate a loop of nothing but the prefill kernel's MFMA sustains, "
+                         "for constant, ternary-code x random and random operands, and exit")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="run only a plain copy kernel of this many MiB (counter calibration)")
     args = ap.parse_args()
@@ -222,6 +241,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.copy_probe:
         return copy_probe(args.copy_probe)
+    if args.mfma_probe:
+        return mfma_probe()
     if args.target_wgs:
         hb.hgf_set_decode_target_workgroups(args.target_wgs)
     use_graph = not args.no_graph

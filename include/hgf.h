@@ -162,6 +162,17 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
 void hgf_profile_enable(int on);
 hgf_status hgf_profile_collect(double *ms_out, long long *launches_out);
 
+/* Measurement aid: the int8 rate the matrix cores sustain on a loop of nothing but the MFMA of
+ * the prefill kernel (operands in registers, no memory traffic, two workgroups of four
+ * wavefronts per compute unit, ten timed launches of `iters` x 32 MFMAs per wavefront after ten
+ * untimed ones), for operand values of kind 0 = all ones, 1 = codes 0..2 against random int8
+ * (this layer's operands), 2 = random int8 on both sides.  The chip lowers its clock under the
+ * matrix cores' switching power, so the rate depends on the values.  Writes tera-operations per
+ * second (2 per multiply-add) and the shader clock in GHz seen by one workgroup (host
+ * pointers).  Allocates and frees its own small device buffers; synchronises the stream.
+ * HGF_ERR_SHAPE for a kind outside 0..2 or iters outside 1..2^20. */
+hgf_status hgf_probe_mfma_rate(int operand_kind, int iters, double *tops_out, double *ghz_out, void *stream);
+
 /* Tuning hook for benchmarks (host state, not thread-safe): how many decode workgroups a
  * launch aims at when it splits d_in across workgroups; 0 restores the default. */
 void hgf_set_decode_target_workgroups(int n);

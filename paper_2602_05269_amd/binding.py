@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
     L.hgf_profile_enable.argtypes = [ci]
     L.hgf_profile_collect.restype = ci
     L.hgf_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_longlong)]
+    L.hgf_probe_mfma_rate.restype = ci
+    L.hgf_probe_mfma_rate.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
     _lib = L
     return L
 
@@ -158,6 +160,15 @@ def hgf_profile_collect():
     n = (ctypes.c_longlong * 2)()
     _check(lib().hgf_profile_collect(ms, n), "hgf_profile_collect")
     return (ms[0], n[0]), (ms[1], n[1])
+
+
+def hgf_probe_mfma_rate(operand_kind: int, iters: int = 800, stream=None) -> Tuple[float, float]:
+    """(int8 TOPS, shader clock in GHz) of a loop of nothing but the prefill kernel's MFMA, for
+    operand values of kind 0 = constant, 1 = codes 0..2 against random int8, 2 = random int8."""
+    tops, ghz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().hgf_probe_mfma_rate(int(operand_kind), int(iters), ctypes.byref(tops), ctypes.byref(ghz),
+                                     _stream(stream)), "hgf_probe_mfma_rate")
+    return tops.value, ghz.value
 
 
 # --------------------------------------------------------------------------- steps

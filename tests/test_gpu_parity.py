@@ -429,3 +429,15 @@ def test_config4_stack_launch_sampled(M, ws):
 @pytest.mark.parametrize("proj", [0, 4, 6])
 def test_config3_prefill_sampled(proj, ws):
     _sampled(3, proj, 2048, ws, n_rows=48, n_tok=24)
+
+
+def test_mfma_rate_probe_runs_and_rejects_bad_arguments():
+    """The measurement aid behind the prefill yardstick: a short run gives a plausible rate and
+    clock; operand kinds outside 0..2 and iteration counts outside 1..2^20 are refused."""
+    tops, ghz = hb.hgf_probe_mfma_rate(1, 50)
+    assert 100.0 < tops < 6000.0, tops
+    assert 0.5 < ghz < 3.0, ghz
+    for kind, iters in ((3, 10), (-1, 10), (0, 0), (0, (1 << 20) + 1)):
+        with pytest.raises(RuntimeError):
+            hb.hgf_probe_mfma_rate(kind, iters)
+
