@@ -337,7 +337,7 @@ def main() -> int:
         torch.cuda.empty_cache()
         # 3B-shape prefill layer, M=2048, the 7 projections of one block
         w3 = Workload(3, 2048, 1, seed=3000, ws=ws)
-        s3 = time_steps(make_runner(w3, ws, False), 3, 1)
+        s3 = time_steps(make_runner(w3, ws, False), 20, 3)
         (_, _), (pms, pn) = kernel_profile(w3, ws, 2)      # two passes; the events bracket grouped launches
         tops = w3.int8_ops / s3 / 1e12
         k_tops = 2 * w3.int8_ops / (pms / 1e3) / 1e12 if pn else 0.0

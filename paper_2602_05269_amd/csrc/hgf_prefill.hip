@@ -44,6 +44,12 @@ struct PrefillParams {
     int32_t *acc_debug;            // single-layer launches only
     int M, Kp, KT, hstride, G;
     int NB;                        // row tiles of all layers
+    int MB;                        // token tiles
+    // Workgroups go to the 8 XCDs round-robin by their index, and each XCD has its own L2: XCD
+    // (xr, xt) of an rx x tx arrangement (rx * tx = 8) takes the row tiles = xr (mod rx) and the
+    // token tiles = xt (mod tx), nbl x mbl of them at most, row tiles first -- so an L2 holds
+    // 1/rx of the weights and sees 1/tx of the activations.
+    int rx, tx, nbl, mbl;
     PrefillLayer L[kMaxGroup];
 };
 
@@ -78,7 +84,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 
     const int tid = threadIdx.x, l = tid & 63, jl = l & 31, hf = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nbg = blockIdx.x % p.NB, mb = blockIdx.x / p.NB;
+    const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+    const int nbg = (within % p.nbl) * p.rx + xcd % p.rx, mb = (within / p.nbl) * p.tx + xcd / p.rx;
+    if (nbg >= p.NB || mb >= p.MB) return;           // padding of the arrangement
     int g = 0;
     while (g + 1 < p.G && nbg >= p.L[g + 1].nb_start) ++g;
     const PrefillLayer &L = p.L[g];
@@ -296,8 +304,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     // Coalesced store path: a token's 64 outputs of this wavefront are 128 contiguous bytes of
     // y.  The fp16 results of 32 tokens at a time are transposed through a wavefront-private
     // LDS patch (32 rows of 128 bytes, 16-byte pieces permuted like the activation tile's) and
-    // leave as 16-byte stores, eight lanes per token.  Needs the whole 64-row strip in range and 16-byte
-    // aligned rows of y; otherwise (ragged d_out, or the int32 debug output) direct stores.
+    // leave as 16-byte stores, eight lanes per token (non-temporal: 13 to 67 MB of output per
+    // launch would otherwise push the weights out of the L2s).  Needs the whole 64-row strip in
+    // range and 16-byte aligned rows of y; otherwise (ragged d_out, or the int32 debug output)
+    // direct stores.
     const bool wide = (N % 8) == 0 && nw0 + 64 <= N && p.acc_debug == nullptr;
     unsigned char *patch = (PM == 64 ? (w < 2 ? xs1 : xs2) : (w < 2 ? xs2 : xs3)) + (w & 1) * 4096;
 
@@ -359,7 +369,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
                 const int tok = i * 8 + (l >> 3), piece = l & 7;
                 const v4u v = *reinterpret_cast<const v4u *>(patch + tok * kTileCols + piece_slot(piece, tok) * 16);
                 const int mm = m0 + tg * 32 + tok;
-                if (mm < p.M) *reinterpret_cast<v4u *>(y + (size_t)mm * N + nw0 + piece * 8) = v;
+                if (mm < p.M) __builtin_nontemporal_store(v, reinterpret_cast<v4u *>(y + (size_t)mm * N + nw0 + piece * 8));
             }
         }
     }
@@ -422,8 +432,19 @@ hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, cons
         const int rounds_narrow = (p.NB * ((M + 63) / 64) + slots - 1) / slots;
         const bool narrow = rounds_narrow * 21 < rounds_wide * 40;
         const int pm = narrow ? 64 : kPM;
-        const int MB = (M + pm - 1) / pm;
-        const dim3 grid(p.NB * MB), block(256);
+        p.MB = (M + pm - 1) / pm;
+        // the arrangement that moves the fewest bytes into the L2s: tx copies of the weights,
+        // rx copies of the quantised activations
+        double wbytes = 0.0;
+        for (int g = 0; g < n; ++g) wbytes += (double)p.L[g].RBn * p.KT * kTileBytes;
+        const double xbytes = (double)M * p.Kp;
+        p.rx = 8;
+        for (int rx = 4; rx >= 1; rx /= 2)
+            if ((8 / rx) * wbytes + rx * xbytes < (8 / p.rx) * wbytes + p.rx * xbytes) p.rx = rx;
+        p.tx = 8 / p.rx;
+        p.nbl = (p.NB + p.rx - 1) / p.rx;
+        p.mbl = (p.MB + p.tx - 1) / p.tx;
+        const dim3 grid(8 * p.nbl * p.mbl), block(256);
 #define HGF_PREFILL(JS)                                                                        \
     do {                                                                                       \
         if (narrow) hipLaunchKernelGGL((prefill_kernel<JS, 64>), grid, block, 0, st, p);       \
