@@ -6,9 +6,10 @@
 // A skinny GEMM on the 32x32x16 f16 MFMA: matrix rows are rank indices (so a lane ends up
 // with four consecutive ranks of one token: 8-byte stores), matrix columns are tokens.
 // One workgroup of four wavefronts owns 32 tokens and one tile of 32 ranks of one layer
-// (blockIdx.y walks the rank tiles of every layer of the group: all layers that read the same
-// activations share one launch, which fills the chip where a single layer's 64 token tiles
-// would not).  x and A are streamed through LDS in
+// (the rank tiles of every layer of the group are numbered through: all layers that read the
+// same activations share one launch, which fills the chip where a single layer's 64 token
+// tiles would not).  On the prefill path the tiles share their launch with the activation
+// quantiser as well (prepare_kernel below).  x and A are streamed through LDS in
 // stretches of KC columns with LDS-direct loads (whole row pieces, coalesced; double
 // buffered, requested one stretch ahead); each wavefront multiplies a quarter of the stretch
 // for every rank tile; the four partial tiles meet in LDS at the end and the first

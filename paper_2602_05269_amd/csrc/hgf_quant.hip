@@ -5,7 +5,10 @@
 // One fp32 reciprocal scale 127/gamma_x per token (IEEE division), one fp32 multiply and
 // a round-half-to-even per element; gamma_x is clamped to >= 1e-5 so a zero token gives
 // zeros.  One workgroup per token: the row is read twice (the second pass hits cache),
-// the int8 row, s_x = gamma_x/127 and sum_k x_q are written once.
+// the int8 row, s_x = gamma_x/127 and sum_k x_q are written once.  This is the stand-alone
+// entry point's kernel and the prefill path's fall-back for rows that are longer than 16384
+// columns or not 16-byte aligned; otherwise that path quantises with one wavefront per token
+// inside prepare_kernel (same arithmetic, row kept in registers).
 #include "hgf_internal.h"
 
 namespace hgf {
