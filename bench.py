@@ -221,7 +221,6 @@ def main() -> int:
     ap.add_argument("--no-secondary", action="store_true", help="skip the secondary cases")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--target-wgs", type=int, default=0, help="decode workgroups per launch (0 = library default)")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="print the int8 rate a loop of nothing but the prefill kernel's MFMA sustains, "
                          "for constant, ternary-code x random and random operands, and exit")
@@ -243,8 +242,6 @@ def main() -> int:
         return copy_probe(args.copy_probe)
     if args.mfma_probe:
         return mfma_probe()
-    if args.target_wgs:
-        hb.hgf_set_decode_target_workgroups(args.target_wgs)
     use_graph = not args.no_graph
 
     ws = hb.Workspace(2048, 11008, 11008, 128)

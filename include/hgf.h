@@ -13,7 +13,8 @@
  *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller unless it is
- *     marked "host".  The library never allocates, frees or keeps a pointer.
+ *     marked "host".  The library never allocates, frees or keeps a pointer (the one
+ *     exception, a measurement aid that is no part of the layer, says so where it is declared).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     only enqueues kernels on that stream: no synchronisation, no host read-back.
  *   - Arguments are validated on the host before anything is enqueued; on error
@@ -140,13 +141,26 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
                               int32_t *acc_debug, void *workspace, size_t workspace_bytes,
                               void *stream);
 
-/* A list of layers run in order on one stream.  Layer i reads slots[src_slot] (fp16
- * [M, d_in]) and writes slots[dst_slot] (fp16 [M, d_out]); consecutive layers with the
- * same src_slot and d_in share one activation quantisation (the q/k/v and up/gate
- * projections of a transformer block read the same input).
+/* Algorithm 1 over a list of layers, run in order on one stream.  The paper's blocks apply
+ * several HGF linears to one input: the attention of Sec. 2.4 (Def. "HGF Attention
+ * Projections": Q, K and V are each Phi_HGF of the same X; the appendix implementation's
+ * attention forward calls the three projections on the same tensor) and its MLP (appendix
+ * implementation, block forward: w1 and w2 both read the normalised block input, w3 reads
+ * their product).  Layer i reads slots[src_slot] (fp16 [M, d_in]) and writes slots[dst_slot]
+ * (fp16 [M, d_out]); consecutive layers with the same src_slot and d_in share one
+ * activation quantisation (steps 1-2 of Algorithm 1 run once for the group).
  *
  *   layers  host array of n_layers descriptions
  *   slots   host array of n_slots device pointers
+ *
+ * For M <= 4 runs of layers execute as persistent launches whose workgroups hand activations
+ * to each other inside the launch.  Such a launch is sized to what an occupancy query says
+ * the device holds at once, and needs the device to itself while it runs: kernels of other
+ * streams that occupy compute units can starve its workgroups, whose bounded waits then run
+ * out (NaN outputs, error word set -- see hgf_workspace_init).  The call cannot see that:
+ * after synchronising, read the int32 at byte offset 8 of the workspace; nonzero means the
+ * outputs of some launch since the last hgf_workspace_init are void.  HGF_ERR_DEVICE is
+ * returned when the runtime refuses a launch (layers enqueued before it have run).
  */
 hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const *slots,
                              int n_slots, int M, void *workspace, size_t workspace_bytes,
@@ -172,10 +186,6 @@ hgf_status hgf_profile_collect(double *ms_out, long long *launches_out);
  * pointers).  Allocates and frees its own small device buffers; synchronises the stream.
  * HGF_ERR_SHAPE for a kind outside 0..2 or iters outside 1..2^20. */
 hgf_status hgf_probe_mfma_rate(int operand_kind, int iters, double *tops_out, double *ghz_out, void *stream);
-
-/* Tuning hook for benchmarks (host state, not thread-safe): how many decode workgroups a
- * launch aims at when it splits d_in across workgroups; 0 restores the default. */
-void hgf_set_decode_target_workgroups(int n);
 
 /* Tuning hook (host state, not thread-safe) for calls with at most 4 tokens, d_in % 8 == 0 and
  * d_in <= 12288.  level 2 (default): hgf_stack_forward runs whole runs of groups of layers as

@@ -100,16 +100,31 @@ def int_gemm(T: np.ndarray, xq: np.ndarray) -> np.ndarray:
     return acc
 
 
+def int_gemm_dense(T: np.ndarray, xq: np.ndarray) -> np.ndarray:
+    """The same accumulators as int_gemm for the full-size configurations, where the triple
+    loop takes minutes: the product of the two integer-valued matrices by the BLAS matmul
+    in fp32.  Exact, whatever order the library sums in: every partial sum is an integer
+    of magnitude <= 127 K, and integers below 2^24 are fp32 numbers.  Pinned against the
+    triple loop on small shapes and on the extreme accumulator by the CPU tests."""
+    N, K = T.shape
+    M, K2 = xq.shape
+    assert K == K2 and 127 * K < (1 << 24)
+    acc = xq.astype(np.float32) @ np.ascontiguousarray(T.astype(np.float32).T)
+    return acc.astype(np.int32)
+
+
 def linear_forward(x: np.ndarray, T: np.ndarray, s_w, A: Optional[np.ndarray],
-                   B: Optional[np.ndarray], alpha: Optional[np.ndarray]) -> Dict[str, np.ndarray]:
+                   B: Optional[np.ndarray], alpha: Optional[np.ndarray],
+                   dense_gemm: bool = False) -> Dict[str, np.ndarray]:
     """Algorithm 1 for one layer.  Returns y (fp64), y16 (its fp16 rounding), the
-    integer intermediates (x_q, s_x, rowsum, acc) and both paths (y_tern, y_corr)."""
+    integer intermediates (x_q, s_x, rowsum, acc) and both paths (y_tern, y_corr).
+    dense_gemm: take step 3 from int_gemm_dense (full-size cases) instead of the loop."""
     M, K = x.shape
     N = T.shape[0]
     r = 0 if A is None else A.shape[0]
     assert r <= MAX_RANK
     xq, s_x, rowsum = quantize_act(x)
-    acc = int_gemm(T, xq)
+    acc = int_gemm_dense(T, xq) if dense_gemm else int_gemm(T, xq)
     xf = np.ascontiguousarray(x.astype(np.float32))
     Af = None if r == 0 else np.ascontiguousarray(A.astype(np.float32))
     Bf = None if r == 0 else np.ascontiguousarray(B.astype(np.float32))

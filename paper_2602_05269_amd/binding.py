@@ -65,8 +65,6 @@ def lib() -> ctypes.CDLL:
     L.hgf_linear_forward.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp, sz, vp]
     L.hgf_stack_forward.restype = ci
     L.hgf_stack_forward.argtypes = [ctypes.POINTER(hgf_layer), ci, ctypes.POINTER(vp), ci, ci, vp, sz, vp]
-    L.hgf_set_decode_target_workgroups.restype = None
-    L.hgf_set_decode_target_workgroups.argtypes = [ci]
     L.hgf_set_single_launch.restype = None
     L.hgf_set_single_launch.argtypes = [ci]
     L.hgf_set_wait_limit.restype = None
@@ -144,10 +142,6 @@ def hgf_set_wait_limit(tries: int) -> None:
     """Test hook: every wait between workgroups of the whole-stack launch gives up after `tries`
     tries (0: the default bound of about a second)."""
     lib().hgf_set_wait_limit(int(tries))
-
-
-def hgf_set_decode_target_workgroups(n: int) -> None:
-    lib().hgf_set_decode_target_workgroups(n)
 
 
 def hgf_profile_enable(on: bool) -> None:

@@ -7,7 +7,7 @@
 
 namespace hgf {
 
-Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
+Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank, int groups, bool with_stack)
 {
     Workspace ws;
     char *p = reinterpret_cast<char *>(base);
@@ -19,17 +19,17 @@ Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank)
     };
     ws.flags = reinterpret_cast<int32_t *>(take(kZeroBytes));
     ws.mail = reinterpret_cast<unsigned char *>(take(2 * kMailBytes));
-    ws.xchg = reinterpret_cast<unsigned char *>(take(2 * kStackSetBytes));
+    ws.xchg = with_stack ? reinterpret_cast<unsigned char *>(take(2 * kStackSetBytes)) : nullptr;
     const int Kp = round_up(d_in, kTileCols);
     ws.xq = reinterpret_cast<int8_t *>(take((size_t)M * Kp));
     ws.s_x = reinterpret_cast<float *>(take((size_t)M * 4));
     ws.rowsum = reinterpret_cast<int32_t *>(take((size_t)M * 4));
     ws.h16_each = align256((size_t)M * h_stride(rank > 0 ? rank : 1) * 2);
-    ws.h16 = reinterpret_cast<_Float16 *>(take(ws.h16_each * kMaxGroup));
+    ws.h16 = reinterpret_cast<_Float16 *>(take(ws.h16_each * groups));
     // two-launch decode path: per layer of a group kMaxHSplit slices of [M, h_stride] partial sums
     const int Md = M < kMaxDecodeM ? M : kMaxDecodeM;
     ws.hslices_each = rank > 0 ? align256((size_t)kMaxHSplit * Md * h_stride(rank) * sizeof(float)) : 0;
-    ws.hslices = reinterpret_cast<float *>(take(ws.hslices_each * kMaxGroup));
+    ws.hslices = reinterpret_cast<float *>(take(ws.hslices_each * groups));
     ws.wsum = reinterpret_cast<double *>(take(size_t(kWsumBlocks) * 8));
     (void)d_out;
     ws.bytes = off;
@@ -368,8 +368,9 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
         return run_large_group(x, M, layers + gr.first, gr.G, ys, nullptr, ws, st);
     };
 
-    // Runs groups [a, b), all stackable, as one persistent launch; false if they do not fit it.
-    auto run_stack = [&](size_t a, size_t b) -> bool {
+    // Runs groups [a, b), all stackable, as one persistent launch.  kNoFit: they do not fit one
+    // (nothing was enqueued; the groups then run one by one); kRefused: the runtime refused it.
+    auto run_stack = [&](size_t a, size_t b) -> Launch {
         StackParams sp;
         sp.M = M;
         sp.nphases = (int)(b - a);
@@ -409,12 +410,12 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
                 act += align256((size_t)M * L.d_out * 2);
             }
         }
-        if (act > kStackActBytes) return false;
+        if (act > kStackActBytes) return Launch::kNoFit;
         sp.act_used = (unsigned)act;
         size_t lds_bytes = 0;
-        if (!plan_stack(sp, &lds_bytes)) return false;
+        if (!plan_stack(sp, &lds_bytes)) return Launch::kNoFit;
         ProfileScope prof(0, st);
-        return launch_stack(sp, lds_bytes, st) == hipSuccess;
+        return launch_stack(sp, lds_bytes, st) == hipSuccess ? Launch::kRan : Launch::kRefused;
     };
 
     size_t gi = 0;
@@ -432,9 +433,13 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
             nl += groups[ge].G;
             ++ge;
         }
-        if (ge - gi >= 2 && run_stack(gi, ge)) {
-            gi = ge;
-            continue;
+        if (ge - gi >= 2) {
+            const Launch r = run_stack(gi, ge);
+            if (r == Launch::kRefused) return HGF_ERR_DEVICE;
+            if (r == Launch::kRan) {
+                gi = ge;
+                continue;
+            }
         }
         if (ge == gi) ge = gi + 1;
         for (; gi < ge; ++gi) {
@@ -468,9 +473,6 @@ hgf_status hgf_profile_collect(double *ms_out, long long *launches_out)
     }
     return HGF_OK;
 }
-
-/* Tuning hook for benchmarks: target number of decode workgroups per launch (0 = default). */
-void hgf_set_decode_target_workgroups(int n) { set_decode_target_wgs(n); }
 
 void hgf_set_single_launch(int level) { g_launch_level = level < 0 ? 0 : (level > 2 ? 2 : level); }
 

@@ -24,15 +24,11 @@ namespace hgf {
 
 namespace {
 
-#ifndef HGF_PF1
-#define HGF_PF1 8
-#endif
-
 // TG: token groups of 32 (1 or 2).
 template <int TG>
 __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 {
-    constexpr int PF = TG == 1 ? HGF_PF1 : 4;       // weight tiles in flight per wavefront
+    constexpr int PF = TG == 1 ? 8 : 4;       // weight tiles in flight per wavefront
     constexpr int XPRE = 4;                         // activation pieces per thread fetched up front
     constexpr int JS = HGF_MAX_RANK / 16;           // steps of the 32x32x16 f16 MFMA over the rank
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -285,13 +281,10 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     }
 }
 
-int g_target_waves = 2048;
+constexpr int kTargetWaves = 2048;            // wavefronts a launch aims at when it splits d_in
 constexpr int kDecodeLdsBudget = 144 * 1024;   // one workgroup of 512 threads per compute unit anyway
 
 }  // namespace
-
-void set_decode_target_wgs(int v) { g_target_waves = v > 0 ? v : 2048; }
-int decode_target_waves() { return g_target_waves; }
 
 // Fills in the launch shape of a group whose layers, activations and outputs are set.
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
@@ -305,10 +298,10 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
         if (p.L[g].hstride > hstride_max) hstride_max = p.L[g].hstride;
     }
     const int tgroups = (M + 31) / 32;
-    // wavefronts per row-block: enough to give the chip `g_target_waves` wavefronts, at most
+    // wavefronts per row-block: enough to give the chip kTargetWaves wavefronts, at most
     // one per tile and eight per workgroup (two per SIMD, so each keeps 256 registers)
     int kw = 1;
-    while (kw < 8 && kw * 2 <= p.KT && rb_total * kw < g_target_waves) kw *= 2;
+    while (kw < 8 && kw * 2 <= p.KT && rb_total * kw < kTargetWaves) kw *= 2;
     p.KW = kw;
     p.RW = kw >= 4 ? 1 : 4 / kw;
     const int nwaves = p.RW * p.KW;

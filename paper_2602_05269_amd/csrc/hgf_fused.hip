@@ -35,10 +35,7 @@ namespace {
 
 constexpr int kStream = 7;             // streaming wavefronts per workgroup (wavefront 7 is the service one)
 constexpr int kXV = 4;                 // 16-byte pieces of a token row per streaming thread: 448*4*8 >= kMaxFusedK
-#ifndef HGF_FUSED_PF
-#define HGF_FUSED_PF 6
-#endif
-constexpr int kPF = HGF_FUSED_PF;      // weight tiles in flight per streaming wavefront.  More than the
+constexpr int kPF = 6;                 // weight tiles in flight per streaming wavefront.  More than the
                                        // bandwidth-delay product needs only lengthens every queue, and with
                                        // it the round trips of the exchange below.
 constexpr int kMaxUnits = 16;          // units per workgroup at most: each has a mailbox slot of its own
@@ -577,7 +574,7 @@ __global__ __launch_bounds__(512) void fused_kernel(FusedParams p)
     }
 }
 
-int g_num_cus = 0;
+int g_num_cus = 0, g_device = -1;
 constexpr size_t kFusedLdsMax = 144 * 1024;
 
 }  // namespace
@@ -588,16 +585,26 @@ constexpr size_t kFusedLdsMax = 144 * 1024;
 // False: the group does not fit this path (too many units per workgroup, or LDS).
 bool plan_fused(FusedParams &p, size_t *lds_bytes)
 {
-    if (g_num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+    // The workgroups exchange partial sums within the launch, so all of them must be resident
+    // at once: at most one per compute unit, and only if the occupancy query confirms that a
+    // unit holds this kernel at its largest LDS request (asked once per device).
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (g_num_cus == 0 || dev != g_device) {
+        int n = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(fused_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax) != hipSuccess) {
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fused_kernel, 512, kFusedLdsMax) != hipSuccess ||
+            per_cu < 1) {
             (void)hipGetLastError();
             return false;
         }
         g_num_cus = n > 0 ? n : 1;
+        g_device = dev;
     }
     const int M = p.M;
     p.Kp = round_up(p.K, kTileCols);

@@ -139,8 +139,11 @@ struct Workspace {
     size_t bytes;        // total bytes needed
 };
 
-// Carves `base` for a call of the given sizes (base may be null: sizes only).
-Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank);
+// Carves `base` for a call of the given sizes (base may be null: sizes only).  `groups`: layers
+// that may share one launch (kMaxGroup for layer lists, 1 for a single layer); `with_stack`:
+// include the exchange regions of the whole-stack launch (else `xchg` is null).
+Workspace carve_workspace(void *base, int M, int d_in, int d_out, int rank, int groups = kMaxGroup,
+                          bool with_stack = true);
 
 __host__ __device__ inline int h_rank_tiles(int rank)   // rank tiles of 16, rounded to a power of two (1, 2, 4, 8)
 {
@@ -265,13 +268,13 @@ hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float
 int prologue_slices(int M, int K);
 hipError_t launch_prologue(ProParams &p, _Float16 *const *h16, hipStream_t st);
 hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st);
+// What a plan or a launch of one of the persistent kernels came to.
+enum class Launch { kRan, kNoFit, kRefused };
 bool plan_fused(FusedParams &p, size_t *lds_bytes);
 hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);
-int decode_target_waves();
 bool plan_stack(StackParams &p, size_t *lds_bytes);
 void set_stack_wait_limit(int tries);
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
-void set_decode_target_wgs(int v);
 hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
                           void *const *ys, int32_t *acc_debug, hipStream_t st);
 

@@ -41,10 +41,7 @@ constexpr int kStream = 8;             // contracting wavefronts per workgroup (
 constexpr int kLoaders = 2;            // loader wavefronts (8, 9): each feeds four contracting ones; 10, 11 serve
 constexpr int kFeed = kStream / kLoaders;
 constexpr int kWaves = kStream + kLoaders + 2;
-#ifndef HGF_STACK_WINDOW
-#define HGF_STACK_WINDOW 3
-#endif
-constexpr int kWindow = HGF_STACK_WINDOW;   // groups of kFeed weight tiles a loader keeps in flight
+constexpr int kWindow = 3;             // groups of kFeed weight tiles a loader keeps in flight
 constexpr int kMinRing = kWindow + 4;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow)
 constexpr int kMaxRing = 48;
 constexpr int kMaxUnits = 16;          // units per workgroup and phase at most
@@ -918,20 +915,16 @@ __global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
     } else {
         // the two serving wavefronts share their SIMDs with contracting ones and are the ones
         // every other workgroup waits for: they issue first
-#ifndef HGF_PRIO
-#define HGF_PRIO 2
-#endif
         if (w == kStream + kLoaders) {
-            if (HGF_PRIO & 1) __builtin_amdgcn_s_setprio(3);
             slice_wave(p, lds, &ctl, c);
         } else {
-            if (HGF_PRIO & 2) __builtin_amdgcn_s_setprio(3);
+            __builtin_amdgcn_s_setprio(3);
             unit_wave(p, lds, &ctl, c);
         }
     }
 }
 
-int g_num_cus = 0;
+int g_num_cus = 0, g_device = -1;
 int g_wait_limit = 0;                  // 0: the default bounds
 constexpr size_t kStackLdsMax = 156 * 1024;   // (the compute unit has 160 KiB; the control words are static)
 
@@ -942,16 +935,27 @@ constexpr size_t kStackLdsMax = 156 * 1024;   // (the compute unit has 160 KiB; 
 // the exchange offsets, the launch shape and the LDS layout.  False: does not fit this path.
 bool plan_stack(StackParams &p, size_t *lds_bytes)
 {
-    if (g_num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+    // The workgroups of this kernel wait for each other, so all of them must be resident at
+    // once: the launch is sized to what the occupancy query says one compute unit holds of this
+    // kernel at its largest LDS request, times the compute units (asked once per device).
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (g_num_cus == 0 || dev != g_device) {
+        int n = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(stack_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStackLdsMax) != hipSuccess) {
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStackLdsMax) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, stack_kernel, 64 * kWaves, kStackLdsMax) !=
+                hipSuccess ||
+            per_cu < 1) {
             (void)hipGetLastError();
             return false;
         }
-        g_num_cus = n > 0 ? n : 1;
+        g_num_cus = n > 0 ? n : 1;              // (one workgroup per compute unit even where two would fit:
+        g_device = dev;                         //  a workgroup is sized to use a whole unit's LDS)
     }
     p.mem_polls = g_wait_limit > 0 ? g_wait_limit : kMemPollsDefault;
     p.lds_polls = g_wait_limit > 0 ? g_wait_limit : kLdsPollsDefault;

@@ -15,10 +15,12 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def assert_close_fp16(y_gpu: np.ndarray, y_ref: np.ndarray, what: str = "y") -> None:
+def assert_close_fp16(y_gpu: np.ndarray, y_ref: np.ndarray, what: str = "y", scale=None) -> None:
+    """Elementwise |y_gpu - y_ref| <= ATOL + RTOL * scale, scale = |y_ref| unless given (a sum of
+    the magnitudes of the two paths, where the output is a small difference of large terms)."""
     y_gpu = y_gpu.astype(np.float64)
     err = np.abs(y_gpu - y_ref)
-    bound = ATOL + RTOL * np.abs(y_ref)
+    bound = ATOL + RTOL * (np.abs(y_ref) if scale is None else scale)
     bad = err > bound
     assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} outside tolerance; worst "
                            f"err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}")
@@ -54,7 +56,10 @@ class GpuLayer:
         torch.cuda.synchronize()
         return y.cpu().numpy(), acc.cpu().numpy()
 
-    def oracle(self, x: np.ndarray, rows=None):
+    def oracle(self, x: np.ndarray, rows=None, dense: bool = False):
+        """The oracle's view of this layer on input x (on the sampled output rows `rows`).
+        dense: the integer contraction by the BLAS product that the CPU tests prove equal
+        to the oracle's triple loop (full-size cases, every element)."""
         c = self.case
         T, A, B, alpha = self.T_ref, c.get("A"), c.get("B"), c.get("alpha")
         if self.rank == 0:
@@ -63,7 +68,7 @@ class GpuLayer:
             T = T[rows]
             if self.rank:
                 B, alpha = B[rows], alpha[rows]
-        return orc.linear_forward(x, T, self.s_w_ref, A, B, alpha)
+        return orc.linear_forward(x, T, self.s_w_ref, A, B, alpha, dense_gemm=dense)
 
     def check_forward(self, x: np.ndarray, rows=None, tokens=None, ws=None):
         y, acc = self.forward(x, ws)

@@ -110,6 +110,25 @@ def test_stack_forward_rejects_bad_wiring_on_the_host():
     assert lib.hgf_stack_forward(layers, 2, slots, 3, 1, 0x100, 4096, None) == 5
 
 
+def test_refused_launch_is_reported_not_hidden():
+    """Where the HIP runtime refuses a launch (here: a host without a GPU, so every launch is
+    refused) the forward calls return HGF_ERR_DEVICE.  In particular a layer list that
+    qualifies for the whole-stack launch must not report success after quietly trying other
+    paths.  Arguments are valid but fake, so this runs only where nothing can be launched."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("needs a host where launches are refused (no GPU)")
+    lib = hb.lib()
+    layers = (hb.hgf_layer * 2)(_layer(src_slot=0, dst_slot=1), _layer(src_slot=1, dst_slot=2))
+    slots = (ctypes.c_void_p * 3)(0x1000, 0x2000, 0x3000)
+    for M in (1, 8, 100):
+        assert lib.hgf_stack_forward(layers, 2, slots, 3, M, 0x100, 1 << 30, None) == 6
+    L = _layer()
+    for M in (1, 8, 100):
+        assert lib.hgf_linear_forward(0x10000, M, ctypes.byref(L), 0x20000, None, 0x30000, 1 << 30, None) == 6
+    assert lib.hgf_workspace_init(0x100, 1 << 30, None) == 6
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(ValueError):

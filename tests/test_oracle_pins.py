@@ -213,6 +213,29 @@ def test_int_gemm_extreme_accumulator():
     assert orc.int_gemm(T, xq).tolist() == [[127 * K, -127 * K]]
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (3, 5, 7), (8, 33, 65), (2, 64, 1365), (17, 130, 4096), (5, 40, 11008)])
+def test_dense_shortcut_equals_the_triple_loop(M, N, K):
+    """The BLAS product used for the full-size parity cases gives the loop's integers exactly:
+    on random operands, on rows of all +1 / all -1 against all +-127 (the largest partial sums
+    there are: 127 K = 1 398 016 < 2^24 at K = 11008), and through linear_forward."""
+    rng = np.random.default_rng(M * 1000 + N * 10 + K)
+    T = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+    xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    T[0] = 1
+    T[N - 1] = -1
+    xq[0] = 127
+    xq[M - 1] = -127
+    loop = orc.int_gemm(T, xq)
+    assert np.array_equal(orc.int_gemm_dense(T, xq), loop)
+    assert abs(int(loop[0, 0])) == 127 * K
+    if K <= 4096:
+        c = synth.make_custom(K + N, M, K, N, 8, act="student_t3")
+        Tc, s_w = orc.ternarize(c["W"])
+        a = orc.linear_forward(c["x"], Tc, s_w, c["A"], c["B"], c["alpha"])
+        b = orc.linear_forward(c["x"], Tc, s_w, c["A"], c["B"], c["alpha"], dense_gemm=True)
+        assert np.array_equal(a["acc"], b["acc"]) and np.array_equal(a["y"], b["y"])
+
+
 # ------------------------------------------------------------------ full layer
 
 def _case(seed, M, K, N, r, **kw):
