@@ -115,8 +115,12 @@ __device__ inline void corr_down_tile(const CorrParams &p, const int bx, const i
     };
 
     // A step waits for its own stage only (the next one stays in flight), meets the others at
-    // a bare barrier, computes, meets them again (everyone is done reading) and requests the
-    // stage after next into the same buffers.
+    // a bare barrier, computes, waits until its LDS reads have RETURNED (the compiler sinks
+    // MFMAs and the waits for their operands below the barrier otherwise, so reads would still
+    // be queued while the buffers are handed over), meets the others again (everyone is done
+    // reading) and requests the stage after next into the same buffers.  The wait matters at
+    // the end of the row: the requests beyond the last stretch are out of range, so their
+    // zeros come back without a memory round trip and would overtake reads still in flight.
     constexpr int kLoads = kXInst + kAInst;     // vector memory operations per wavefront and stage
     constexpr int kWaitNextInFlight = (kLoads & 0xF) | (7 << 4) | (15 << 8) | ((kLoads >> 4) << 14);
 #define HGF_CSTEP(XC, AC, ST)                                  \
@@ -126,6 +130,7 @@ __device__ inline void corr_down_tile(const CorrParams &p, const int bx, const i
         __builtin_amdgcn_s_barrier();                          \
         asm volatile("" ::: "memory");                         \
         compute(XC, AC);                                       \
+        __builtin_amdgcn_s_waitcnt(0xC07F);     /* lgkmcnt(0) */ \
         asm volatile("" ::: "memory");                         \
         __builtin_amdgcn_s_barrier();                          \
         asm volatile("" ::: "memory");                         \

@@ -22,8 +22,13 @@ def assert_close_fp16(y_gpu: np.ndarray, y_ref: np.ndarray, what: str = "y", sca
     err = np.abs(y_gpu - y_ref)
     bound = ATOL + RTOL * (np.abs(y_ref) if scale is None else scale)
     bad = err > bound
-    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} outside tolerance; worst "
-                           f"err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}")
+    if bad.any():
+        idx = np.argwhere(bad)
+        where = ", ".join(f"axis {a}: {len(np.unique(idx[:, a]))} distinct in [{idx[:, a].min()}, {idx[:, a].max()}]"
+                          for a in range(idx.shape[1]))
+        worst = np.unravel_index(err.argmax(), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} outside tolerance ({where}); worst err "
+                             f"{err.max():.3e} at {worst}: got {y_gpu[worst]!r}, reference {y_ref[worst]!r}")
 
 
 class GpuLayer:
