@@ -141,6 +141,29 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
                               int32_t *acc_debug, void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* hgf_linear_forward for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and same results as hgf_linear_forward, but what the workspace
+ * holds there (launch counter, exchange buffers, x_q, token scales, SiLU(A x), partial sums)
+ * lives in a fixed array inside the library's device image: hgf_static_scratch_bytes() bytes
+ * (8 MiB) on every GPU the library runs on, held until the process ends.  The call allocates
+ * and frees nothing (no hipMalloc, no hipFree, no allocating library routine).
+ *
+ * Limit: hgf_static_scratch_needed(M, d_in, d_out, rank) <= hgf_static_scratch_bytes(), roughly
+ * M * pad128(d_in) + 1 KiB * M (+ 16 KiB * min(M, 40) for M <= 40) + 0.3 MiB: e.g. any d_in at
+ * M <= 64, or d_in <= 3072 at M = 2048.  Beyond it: HGF_ERR_WORKSPACE, nothing enqueued.
+ * The first call on a GPU (with that GPU current) looks up the array's address there and
+ * enqueues two small fill kernels on `stream` that prepare it, as hgf_workspace_init does for a
+ * workspace.  Every call on a GPU shares that GPU's array, which keeps what the last call left:
+ * each call rewrites what it reads, and the launch counter and exchange buffers are handed on
+ * in a consistent state -- provided calls on one GPU do not overlap.  Calls must be ordered
+ * (one stream, or events between streams); concurrent calls on one GPU race on the array.
+ * Other entry points and other workspaces are not affected. */
+size_t hgf_static_scratch_bytes(void);
+size_t hgf_static_scratch_needed(int M, int d_in, int d_out, int rank);   /* 0 on invalid sizes */
+hgf_status hgf_linear_forward_static(const void *x_f16, int M, const hgf_layer *L, void *y_f16,
+                                     int32_t *acc_debug, void *stream);
+
 /* Algorithm 1 over a list of layers, run in order on one stream.  The paper's blocks apply
  * several HGF linears to one input: the attention of Sec. 2.4 (Def. "HGF Attention
  * Projections": Q, K and V are each Phi_HGF of the same X; the appendix implementation's

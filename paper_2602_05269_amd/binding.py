@@ -63,6 +63,12 @@ def lib() -> ctypes.CDLL:
     L.hgf_quantize_activations.argtypes = [vp, ci, ci, vp, vp, vp, vp]
     L.hgf_linear_forward.restype = ci
     L.hgf_linear_forward.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp, sz, vp]
+    L.hgf_static_scratch_bytes.restype = sz
+    L.hgf_static_scratch_bytes.argtypes = []
+    L.hgf_static_scratch_needed.restype = sz
+    L.hgf_static_scratch_needed.argtypes = [ci, ci, ci, ci]
+    L.hgf_linear_forward_static.restype = ci
+    L.hgf_linear_forward_static.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp]
     L.hgf_stack_forward.restype = ci
     L.hgf_stack_forward.argtypes = [ctypes.POINTER(hgf_layer), ci, ctypes.POINTER(vp), ci, ci, vp, sz, vp]
     L.hgf_set_single_launch.restype = None
@@ -233,6 +239,28 @@ def hgf_linear_forward(x: torch.Tensor, layer: Layer, ws: Workspace, y: Optional
         y = torch.empty((M, layer.d_out), dtype=torch.float16, device=x.device)
     _check(lib().hgf_linear_forward(x.data_ptr(), M, ctypes.byref(layer.c), y.data_ptr(), _ptr(acc_debug),
                                     ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_linear_forward")
+    return y
+
+
+def hgf_static_scratch_bytes() -> int:
+    return lib().hgf_static_scratch_bytes()
+
+
+def hgf_static_scratch_needed(M: int, d_in: int, d_out: int, rank: int) -> int:
+    return lib().hgf_static_scratch_needed(M, d_in, d_out, rank)
+
+
+def hgf_linear_forward_static(x: torch.Tensor, layer: Layer, y: torch.Tensor,
+                              acc_debug: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hgf_linear_forward without a workspace (the library's own fixed scratch): `y` is the
+    caller's output tensor, nothing is allocated here or in the library."""
+    _dev(x, torch.float16, "x")
+    _dev(y, torch.float16, "y")
+    M, d_in = x.shape
+    if d_in != layer.d_in or tuple(y.shape) != (M, layer.d_out):
+        raise ValueError("x or y has the wrong shape")
+    _check(lib().hgf_linear_forward_static(x.data_ptr(), M, ctypes.byref(layer.c), y.data_ptr(), _ptr(acc_debug),
+                                           _stream(stream)), "hgf_linear_forward_static")
     return y
 
 

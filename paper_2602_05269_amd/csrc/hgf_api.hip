@@ -203,6 +203,54 @@ hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G,
     return from_hip(launch_prefill(ws, h16, M, layers, G, ys, acc_debug, st));
 }
 
+// ---- the scratch of hgf_linear_forward_static: what the workspace argument brings to
+//      hgf_linear_forward (launch counter, exchange buffers, x_q, scales, SiLU(A x), partial
+//      sums), for callers that can bring none.  Every GPU the library runs on holds its own
+//      copy of this array at its own address until the process ends; host code reaches it only
+//      through the address hipGetSymbolAddress returns with that GPU current.
+constexpr size_t kStaticScratchBytes = size_t(8) << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+}  // namespace hgf
+
+static __device__ __align__(256) unsigned char scratch[hgf::kStaticScratchBytes];
+
+namespace hgf {
+namespace {
+
+unsigned char *g_scratch_ptr[kMaxDevices];      // per device: the array's address there (null: not asked yet)
+
+Workspace carve_static(void *base, int M, const hgf_layer *L)
+{
+    return carve_workspace(base, M, L->d_in, L->d_out, L->rank, /*groups=*/1, /*with_stack=*/false);
+}
+
+// The device address of `scratch` on the current device, set up on first use: the address is
+// looked up and the control words and exchange buffers are put into the state
+// hgf_workspace_init leaves them in (fill kernels on `st`, ahead of the caller's work).
+hgf_status static_scratch(hipStream_t st, unsigned char **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return HGF_ERR_DEVICE;
+    }
+    if (!g_scratch_ptr[dev]) {
+        unsigned char *ptr = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return HGF_ERR_DEVICE;
+        }
+        const Workspace ws = carve_workspace(ptr, 1, 1, 1, 0, 1, false);
+        if (launch_fill(ws.flags, align256(kZeroBytes), 0u, st) != hipSuccess ||
+            launch_fill(ws.mail, 2 * kMailBytes, 0xFFFFFFFFu, st) != hipSuccess)
+            return HGF_ERR_DEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HGF_OK;
+}
+
 }  // namespace
 }  // namespace hgf
 
@@ -304,6 +352,36 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
     }
     void *ys1[1] = {y_f16};
     return run_large_group(x_f16, M, L, 1, ys1, acc_debug, ws, st);
+}
+
+size_t hgf_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+size_t hgf_static_scratch_needed(int M, int d_in, int d_out, int rank)
+{
+    if (!dims_ok(d_in, d_out) || rank < 0 || rank > HGF_MAX_RANK || !tokens_ok(M, d_in, d_out)) return 0;
+    return carve_workspace(nullptr, M, d_in, d_out, rank, 1, false).bytes;
+}
+
+hgf_status hgf_linear_forward_static(const void *x_f16, int M, const hgf_layer *L, void *y_f16, int32_t *acc_debug,
+                                     void *stream)
+{
+    if (!x_f16 || !y_f16) return HGF_ERR_NULL;
+    const hgf_status s = check_layer(L, M);
+    if (s != HGF_OK) return s;
+    if (!aligned16(x_f16) || !aligned16(y_f16) || (acc_debug && !aligned16(acc_debug))) return HGF_ERR_ALIGN;
+    if (carve_static(nullptr, M, L).bytes > kStaticScratchBytes) return HGF_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *base = nullptr;
+    const hgf_status ss = static_scratch(st, &base);
+    if (ss != HGF_OK) return ss;
+    const Workspace ws = carve_static(base, M, L);
+    void *ys[1] = {y_f16};
+    const bool profiling = g_profile;           // (the profiling aid creates events: not from here)
+    g_profile = false;
+    const hgf_status r = M <= kMaxDecodeM ? run_decode_group(x_f16, M, L, 1, ys, acc_debug, ws, st)
+                                          : run_large_group(x_f16, M, L, 1, ys, acc_debug, ws, st);
+    g_profile = profiling;
+    return r;
 }
 
 hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const *slots, int n_slots, int M,
