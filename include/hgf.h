@@ -141,6 +141,31 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
                               int32_t *acc_debug, void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* The gated pair of the paper's MLP (appendix implementation, block forward:
+ * x + w3(SiLU(w1(n2 x)) * w2(n2 x)); w1, w2, w3 are HGF linears): both projections of one input
+ * and their product in one pass,
+ *
+ *     z[m, n] = SiLU(y_gate[m, n]) * y_up[m, n],      SiLU(v) = v * sigmoid(v),
+ *
+ * with y_gate and y_up the outputs of Algorithm 1 for the layers `gate` (w1) and `up` (w2) on
+ * the same x: one activation quantisation serves both, each workgroup contracts the same rows of
+ * both weight matrices, and the two fp32 results meet in registers or LDS -- neither y is
+ * rounded to fp16 or written to memory; z is rounded to fp16 once.  z is the input of the
+ * down projection (w3), an ordinary hgf_linear_forward.
+ *
+ *   x_f16           fp16 [M, d_in]
+ *   gate, up        host pointers; same d_in and d_out; ranks may differ (for M > 40 they must
+ *                   pad to the same multiple-of-32 width, else HGF_ERR_UNSUPPORTED)
+ *   z_f16           fp16 [M, d_out], written
+ *   amax_out        fp32 [M] or NULL: per-token max_n |z[m, n]| of the stored fp16 values -- the
+ *                   gamma_x of Algorithm 1 step 1 for the layer that reads z
+ *   acc_debug_gate, acc_debug_up   int32 [M, d_out] or NULL: the exact accumulators of step 3
+ */
+hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, const hgf_layer *up,
+                              void *z_f16, float *amax_out, int32_t *acc_debug_gate,
+                              int32_t *acc_debug_up, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
 /* hgf_linear_forward for callers that cannot allocate device memory and have no workspace to
  * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, same kernels and same results as hgf_linear_forward, but what the workspace

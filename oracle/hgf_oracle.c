@@ -134,3 +134,13 @@ void hgf_oracle_epilogue(const float *x, const int32_t *acc, const float *s_x, f
         }
     }
 }
+
+/* The gated product of the paper's MLP (appendix implementation, block forward:
+ * x + w3(SiLU(w1(n2 x)) * w2(n2 x))): elementwise z = SiLU(y_gate) * y_up with
+ * SiLU(v) = v * sigmoid(v) (Sec. 2.3, Def. "Low-Rank Correction", states the activation),
+ * in fp64 on the two layers' un-rounded outputs. */
+void hgf_oracle_swiglu(const double *y_gate, const double *y_up, long M, long N, double *z)
+{
+    for (long i = 0; i < M * N; ++i)
+        z[i] = (y_gate[i] / (1.0 + exp(-y_gate[i]))) * y_up[i];
+}

@@ -141,6 +141,29 @@ def linear_forward(x: np.ndarray, T: np.ndarray, s_w, A: Optional[np.ndarray],
             "acc": acc, "y_tern": yt, "y_corr": yc}
 
 
+def swiglu(y_gate: np.ndarray, y_up: np.ndarray) -> np.ndarray:
+    """z = SiLU(y_gate) * y_up elementwise in fp64 (appendix implementation, block forward)."""
+    yg = np.ascontiguousarray(y_gate, dtype=np.float64)
+    yu = np.ascontiguousarray(y_up, dtype=np.float64)
+    assert yg.shape == yu.shape and yg.ndim == 2
+    z = np.empty_like(yg)
+    _load().hgf_oracle_swiglu(_p(yg), _p(yu), ctypes.c_long(yg.shape[0]), ctypes.c_long(yg.shape[1]), _p(z))
+    return z
+
+
+def swiglu_pair_forward(x: np.ndarray, gate: Dict, up: Dict, dense_gemm: bool = False) -> Dict[str, np.ndarray]:
+    """The gated pair of the paper's MLP: both HGF linears (Algorithm 1) on the same x, then
+    z = SiLU(y_gate) * y_up on their UN-rounded outputs; z16 is z rounded to fp16 once, amax the
+    per-token max |z16| (step 1 of Algorithm 1 for the layer that reads z16), as fp32.
+    `gate` and `up` hold T, s_w, A, B, alpha."""
+    g = linear_forward(x, gate["T"], gate["s_w"], gate.get("A"), gate.get("B"), gate.get("alpha"), dense_gemm)
+    u = linear_forward(x, up["T"], up["s_w"], up.get("A"), up.get("B"), up.get("alpha"), dense_gemm)
+    z = swiglu(g["y"], u["y"])
+    z16 = z.astype(np.float16)
+    return {"z": z, "z16": z16, "amax": np.abs(z16).max(axis=1).astype(np.float32),
+            "gate": g, "up": u}
+
+
 def stack_forward(layers: Sequence[Dict], wiring: Sequence[Tuple[int, int]],
                   x0: np.ndarray) -> List[np.ndarray]:
     """A chain of HGF linears: layer i reads slot wiring[i][0] and writes slot

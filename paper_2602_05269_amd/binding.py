@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.hgf_static_scratch_needed.argtypes = [ci, ci, ci, ci]
     L.hgf_linear_forward_static.restype = ci
     L.hgf_linear_forward_static.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp]
+    L.hgf_swiglu_forward.restype = ci
+    L.hgf_swiglu_forward.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), ctypes.POINTER(hgf_layer), vp, vp, vp, vp, vp, sz, vp]
     L.hgf_stack_forward.restype = ci
     L.hgf_stack_forward.argtypes = [ctypes.POINTER(hgf_layer), ci, ctypes.POINTER(vp), ci, ci, vp, sz, vp]
     L.hgf_set_single_launch.restype = None
@@ -240,6 +242,24 @@ def hgf_linear_forward(x: torch.Tensor, layer: Layer, ws: Workspace, y: Optional
     _check(lib().hgf_linear_forward(x.data_ptr(), M, ctypes.byref(layer.c), y.data_ptr(), _ptr(acc_debug),
                                     ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_linear_forward")
     return y
+
+
+def hgf_swiglu_forward(x: torch.Tensor, gate: Layer, up: Layer, ws: Workspace, z: Optional[torch.Tensor] = None,
+                       amax: Optional[torch.Tensor] = None, acc_debug_gate: Optional[torch.Tensor] = None,
+                       acc_debug_up: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """z = SiLU(gate(x)) * up(x) for two HGF linears of one shape, fp16 [M, d_out]."""
+    _dev(x, torch.float16, "x")
+    M, d_in = x.shape
+    if d_in != gate.d_in or d_in != up.d_in or gate.d_out != up.d_out:
+        raise ValueError("gate and up must share d_in and d_out with x")
+    if z is None:
+        z = torch.empty((M, up.d_out), dtype=torch.float16, device=x.device)
+    if amax is not None:
+        _dev(amax, torch.float32, "amax")
+    _check(lib().hgf_swiglu_forward(x.data_ptr(), M, ctypes.byref(gate.c), ctypes.byref(up.c), z.data_ptr(),
+                                    _ptr(amax), _ptr(acc_debug_gate), _ptr(acc_debug_up), ws.buf.data_ptr(),
+                                    ws.bytes, _stream(stream)), "hgf_swiglu_forward")
+    return z
 
 
 def hgf_static_scratch_bytes() -> int:

@@ -101,11 +101,16 @@ struct ProfileScope {
 
 // Decode (M <= kMaxDecodeM): `G` layers that read the same activations `x` run as two launches:
 // the fused prologue (quantiser + partial sums of every A x) and one grouped main kernel.
+//
+// `pair` (G == 2): the SwiGLU pair -- layers[0] is the gate projection, layers[1] the up
+// projection; the one output ys[1] receives SiLU(y_gate) * y_up, amax_out (nullable) the
+// per-token max of its magnitude, acc_debug2 (nullable) the up projection's accumulators.
 hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
-                            int32_t *acc_debug, const Workspace &ws, hipStream_t st)
+                            int32_t *acc_debug, const Workspace &ws, hipStream_t st, bool pair = false,
+                            float *amax_out = nullptr, int32_t *acc_debug2 = nullptr)
 {
     const int K = layers[0].d_in;
-    bool fused = g_launch_level >= 1 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
+    bool fused = !pair && g_launch_level >= 1 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
     for (int g = 0; g < G; ++g)
         fused = fused && (layers[g].rank == 0 ||
                           (layers[g].rank % 8 == 0 && aligned16(layers[g].A_f16) && aligned16(layers[g].B_f16) &&
@@ -145,6 +150,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     pp.xq = ws.xq;
     pp.s_x = ws.s_x;
     pp.rowsum = ws.rowsum;
+    pp.amax_zero = pair ? amax_out : nullptr;
     pp.M = M;
     pp.K = K;
     pp.Kp = round_up(K, kTileCols);
@@ -155,6 +161,8 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     dp.rowsum = ws.rowsum;
     dp.M = M;
     dp.G = G;
+    dp.pair = pair ? 1 : 0;
+    dp.amax_out = pair ? amax_out : nullptr;
     for (int g = 0; g < G; ++g) {
         const hgf_layer &L = layers[g];
         float *slices = reinterpret_cast<float *>(reinterpret_cast<char *>(ws.hslices) + ws.hslices_each * g);
@@ -169,7 +177,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
         D.h16 = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
         D.y = reinterpret_cast<_Float16 *>(ys[g]);
-        D.acc_debug = acc_debug;
+        D.acc_debug = (pair && g == 1) ? acc_debug2 : acc_debug;
         D.N = L.d_out;
         D.RBn = round_up(L.d_out, kTileRows) / kTileRows;
         D.rank = L.rank;
@@ -186,7 +194,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
 // and the down-projections with SiLU of all layers (both read x), then one launch of the int8
 // MFMA prefill kernel over the tiles of all layers.
 hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G, void *const *ys,
-                           int32_t *acc_debug, const Workspace &ws, hipStream_t st)
+                           int32_t *acc_debug, const Workspace &ws, hipStream_t st, const PairOut *pair_out = nullptr)
 {
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(x);
     const int K = layers[0].d_in;
@@ -198,9 +206,12 @@ hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G,
         rank[g] = layers[g].rank;
         h16[g] = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
     }
+    if (pair_out && pair_out->amax_out &&
+        launch_zero_words(pair_out->amax_out, (size_t)M, st) != hipSuccess)
+        return HGF_ERR_DEVICE;
     if (launch_corr_down(xh, M, K, G, A, rank, h16, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess) return HGF_ERR_DEVICE;
     ProfileScope prof(1, st);
-    return from_hip(launch_prefill(ws, h16, M, layers, G, ys, acc_debug, st));
+    return from_hip(launch_prefill(ws, h16, M, layers, G, ys, acc_debug, st, pair_out));
 }
 
 // ---- the scratch of hgf_linear_forward_static: what the workspace argument brings to
@@ -352,6 +363,35 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
     }
     void *ys1[1] = {y_f16};
     return run_large_group(x_f16, M, L, 1, ys1, acc_debug, ws, st);
+}
+
+hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, const hgf_layer *up, void *z_f16,
+                              float *amax_out, int32_t *acc_debug_gate, int32_t *acc_debug_up, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!x_f16 || !z_f16) return HGF_ERR_NULL;
+    hgf_status s = check_layer(gate, M);
+    if (s == HGF_OK) s = check_layer(up, M);
+    if (s != HGF_OK) return s;
+    if (gate->d_in != up->d_in || gate->d_out != up->d_out) return HGF_ERR_SHAPE;
+    if (!aligned16(x_f16) || !aligned16(z_f16) || (acc_debug_gate && !aligned16(acc_debug_gate)) ||
+        (acc_debug_up && !aligned16(acc_debug_up)) || (reinterpret_cast<uintptr_t>(amax_out) & 3u))
+        return HGF_ERR_ALIGN;
+    if (!workspace) return HGF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return HGF_ERR_ALIGN;
+    const int rank_max = gate->rank > up->rank ? gate->rank : up->rank;
+    const Workspace ws = carve_workspace(workspace, M, gate->d_in, gate->d_out, rank_max);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    // the prefill kernel stages both layers' SiLU(A x) at one row width
+    if (M > kMaxDecodeM && gate->rank > 0 && up->rank > 0 && h_stride(gate->rank) != h_stride(up->rank))
+        return HGF_ERR_UNSUPPORTED;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const hgf_layer pairL[2] = {*gate, *up};
+    void *ys[2] = {nullptr, z_f16};
+    if (M <= kMaxDecodeM)
+        return run_decode_group(x_f16, M, pairL, 2, ys, acc_debug_gate, ws, st, true, amax_out, acc_debug_up);
+    const PairOut po = {acc_debug_up, amax_out};
+    return run_large_group(x_f16, M, pairL, 2, ys, acc_debug_gate, ws, st, &po);
 }
 
 size_t hgf_static_scratch_bytes(void) { return kStaticScratchBytes; }

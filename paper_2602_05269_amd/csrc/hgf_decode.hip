@@ -37,18 +37,20 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // this workgroup's layer: every candidate is read at a fixed kernel-argument offset (one
     // batch of scalar loads) and selected, instead of a dependent load at a computed offset
+    const int rw = w / p.KW, kw = w % p.KW;
+    const bool pair = p.pair != 0;
     DecLayer L = p.L[0];
     int wg0 = 0;
 #pragma unroll
     for (int i = 1; i < kMaxGroup; ++i) {
-        if (i < p.G && (int)blockIdx.x >= p.wg_start[i]) {
+        if (i < p.G && (pair ? rw == i : (int)blockIdx.x >= p.wg_start[i])) {
             L = p.L[i];
-            wg0 = p.wg_start[i];
+            wg0 = pair ? 0 : p.wg_start[i];
         }
     }
-    const int rw = w / p.KW, kw = w % p.KW;
-    const int rb_first = ((int)blockIdx.x - wg0) * p.RW;   // first row-block of the workgroup
-    const int rb = rb_first + rw;                          // this wavefront's row-block
+    // first row-block of the workgroup and this wavefront's (pair: the same one in both layers)
+    const int rb_first = pair ? (int)blockIdx.x : ((int)blockIdx.x - wg0) * p.RW;
+    const int rb = pair ? rb_first : rb_first + rw;
     const bool rb_ok = rb < L.RBn;
     const int mcount = p.M;                          // tokens (<= 32*TG)
     const int jl = l & 31, hf = l >> 5;              // matrix column / row index, and k-half
@@ -57,12 +59,15 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 
     // ---- (1) SiLU(A x) of the tokens, fp16 rows of hstride (a small kernel has added the slices
     //      of the prologue): 16 bytes per thread and request
+    //      (pair: each half of the workgroup brings its own layer's rows)
     constexpr int HV = 2;                            // 512 x 2 x 8 halves >= 64 tokens x 128 ranks
+    const int hthreads = pair ? nthreads / 2 : nthreads;
+    const int htid = pair ? tid - rw * hthreads : tid;
     const int htotal = L.rank > 0 ? mcount * L.hstride : 0;
     const rsrc_t hr = make_rsrc(L.h16, (unsigned)htotal * 2u);
     v4u hpre[HV];
 #pragma unroll
-    for (int u = 0; u < HV; ++u) hpre[u] = buf_load16(hr, (unsigned)(tid + u * nthreads) * 16u, (tid + u * nthreads) * 8 < htotal);
+    for (int u = 0; u < HV; ++u) hpre[u] = buf_load16(hr, (unsigned)(htid + u * hthreads) * 16u, (htid + u * hthreads) * 8 < htotal);
 
     // ---- (2) the first pieces of the quantised activations (16 bytes each)
     const int cend0 = min(p.CT, p.KT);
@@ -83,9 +88,17 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     //      token scales of the wavefront that owns the row-block
     float alpha_pre;
     {
-        const rsrc_t ar = make_rsrc(L.alpha, L.rank > 0 ? (unsigned)L.N * 2u : 0u);
-        const int n = rb_first * kTileRows + tid;
-        alpha_pre = (float)half_bits(buf_load2(ar, (unsigned)n * 2u, tid < p.RW * kTileRows && n < L.N));
+        // thread t < 32 RW takes row t of the workgroup's rows; in a pair threads 0..31 take the
+        // rows of layer 0 and threads 32..63 the same rows of layer 1 (two guarded requests with
+        // uniform descriptors and a select: a per-lane descriptor would be a loop)
+        const DecLayer &L0 = pair ? p.L[0] : L;
+        const rsrc_t ar0 = make_rsrc(L0.alpha, L0.rank > 0 ? (unsigned)L0.N * 2u : 0u);
+        const rsrc_t ar1 = make_rsrc(p.L[1].alpha, pair && p.L[1].rank > 0 ? (unsigned)p.L[1].N * 2u : 0u);
+        const int n = rb_first * kTileRows + (pair ? (tid & (kTileRows - 1)) : tid);
+        const bool first = !pair || tid < kTileRows;
+        const float a0 = (float)half_bits(buf_load2(ar0, (unsigned)n * 2u, first && tid < p.RW * kTileRows && n < L0.N));
+        const float a1 = (float)half_bits(buf_load2(ar1, (unsigned)n * 2u, !first && tid < p.RW * kTileRows && n < p.L[1].N));
+        alpha_pre = first ? a0 : a1;
     }
     v8h breg[JS];
     {
@@ -125,14 +138,17 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     }
 
     // ---- SiLU(A x) of the tokens and tanh(alpha) into LDS
-    _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off);
+    _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off + (pair ? rw * p.h_each : 0));
     float *gs = reinterpret_cast<float *>(lds + p.g_off);
 #pragma unroll
     for (int u = 0; u < HV; ++u)
-        if ((tid + u * nthreads) * 8 < htotal) *reinterpret_cast<v4u *>(hs + (tid + u * nthreads) * 8) = hpre[u];
-    for (int v = tid + HV * nthreads; v * 8 < htotal; v += nthreads)   // workgroups of 256 threads, many tokens
+        if ((htid + u * hthreads) * 8 < htotal) *reinterpret_cast<v4u *>(hs + (htid + u * hthreads) * 8) = hpre[u];
+    for (int v = htid + HV * hthreads; v * 8 < htotal; v += hthreads)   // few threads, many tokens
         *reinterpret_cast<v4u *>(hs + v * 8) = buf_load16(hr, (unsigned)v * 16u);
-    if (tid < p.RW * kTileRows) gs[tid] = L.rank > 0 ? tanhf(alpha_pre) : 0.f;
+    if (tid < p.RW * kTileRows) {
+        const int grank = pair ? (tid >= kTileRows ? p.L[1].rank : p.L[0].rank) : L.rank;
+        gs[tid] = grank > 0 ? tanhf(alpha_pre) : 0.f;
+    }
 
     v16i acc[TG];
 #pragma unroll
@@ -216,19 +232,25 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
             for (int tg = 0; tg < TG; ++tg) red[((slot0 * TG) + tg) * 64 + l] = acc[tg];
         }
         __syncthreads();
-        if (kw > 0) return;
-        for (int o = 1; o < p.KW; ++o) {
+        if (kw > 0 && !pair) return;
+        if (kw == 0) {
+            for (int o = 1; o < p.KW; ++o) {
 #pragma unroll
-            for (int tg = 0; tg < TG; ++tg) acc[tg] += red[(((slot0 + o) * TG) + tg) * 64 + l];
+                for (int tg = 0; tg < TG; ++tg) acc[tg] += red[(((slot0 + o) * TG) + tg) * 64 + l];
+            }
         }
     }
-    if (!rb_ok || n0 >= L.N) return;
+    if (pair && p.KW == 1) __syncthreads();          // (pair: the staged activations give way to the exchange)
+    // live: this wavefront finishes a row-block.  In a pair every wavefront stays for the
+    // barrier over which the gate's outputs pass to the wavefront that holds the up rows.
+    const bool live = kw == 0 && rb_ok && n0 < L.N;
+    if (!live && !pair) return;
 
     // ---- correction up-projection: corr[m,n] = sum_j B[n,j] h[m,j] on the f16 MFMA
     v16f corr[TG];
 #pragma unroll
     for (int tg = 0; tg < TG; ++tg) corr[tg] = (v16f){};
-    if (L.rank > 0) {
+    if (live && L.rank > 0) {
 #pragma unroll
         for (int js = 0; js < JS; ++js) {
             if (js * 16 < L.hstride) {
@@ -246,36 +268,61 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 
     // ---- dequantise, gate, store.  Element 4*q + v of a lane's accumulator is row
     //      8*q + 4*hf + v of the row-block, for the token of the lane.
+    //      Pair: the wavefront with the gate rows leaves its fp32 outputs in LDS; after a barrier
+    //      the wavefront with the same rows of `up` (same lanes, same elements) multiplies its own
+    //      by SiLU of them -- neither layer's output goes to memory -- and stores the product.
     const bool nvec = (L.N % 4) == 0;
+    float *exch = reinterpret_cast<float *>(lds + p.exch_off);
+    for (int pass = 0; pass < (pair ? 2 : 1); ++pass) {
+        if (pair && pass == 1) __syncthreads();
+        if (!live || (pair && rw != pass)) continue;
+        const bool gate_side = pair && rw == 0;
 #pragma unroll
-    for (int tg = 0; tg < TG; ++tg) {
-        const int m = tg * 32 + jl;
-        if (m >= mcount) continue;
-        const float scale = sx_pre[tg] * s_w;
-        const int rs = rs_pre[tg];
+        for (int tg = 0; tg < TG; ++tg) {
+            const int m = tg * 32 + jl;
+            const bool m_ok = m < mcount;
+            const float scale = sx_pre[tg] * s_w;
+            const int rs = rs_pre[tg];
+            float zmax = 0.f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int r0 = 8 * q + 4 * hf;           // first of 4 consecutive rows within the row-block
-            const int nl = n0 + r0;
-            int a[4];
-            v4h o;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                a[v] = acc[tg][4 * q + v] - rs;
-                o[v] = (_Float16)((float)a[v] * scale + gs[rw * kTileRows + r0 + v] * corr[tg][4 * q + v]);
-            }
-            const size_t at = (size_t)m * L.N + nl;
-            if (nvec && nl + 3 < L.N) {
-                *reinterpret_cast<v4h *>(L.y + at) = o;
-                if (L.acc_debug) *reinterpret_cast<v4i *>(L.acc_debug + at) = (v4i){a[0], a[1], a[2], a[3]};
-            } else {
+            for (int q = 0; q < 4; ++q) {
+                const int r0 = 8 * q + 4 * hf;           // first of 4 consecutive rows within the row-block
+                const int nl = n0 + r0;
+                int a[4];
+                v4h o;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    if (nl + v < L.N) {
-                        L.y[at + v] = o[v];
-                        if (L.acc_debug) L.acc_debug[at + v] = a[v];
+                    a[v] = acc[tg][4 * q + v] - rs;
+                    float yv = (float)a[v] * scale + gs[rw * kTileRows + r0 + v] * corr[tg][4 * q + v];
+                    if (gate_side) {
+                        exch[(tg * 16 + 4 * q + v) * 64 + l] = yv;
+                    } else if (pair) {
+                        yv = silu(exch[(tg * 16 + 4 * q + v) * 64 + l]) * yv;
+                    }
+                    o[v] = (_Float16)yv;
+                    if (nl + v < L.N) zmax = fmaxf(zmax, fabsf((float)o[v]));
+                }
+                if (!m_ok) continue;
+                const size_t at = (size_t)m * L.N + nl;
+                if (nvec && nl + 3 < L.N) {
+                    if (!gate_side) *reinterpret_cast<v4h *>(L.y + at) = o;
+                    if (L.acc_debug) *reinterpret_cast<v4i *>(L.acc_debug + at) = (v4i){a[0], a[1], a[2], a[3]};
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if (nl + v < L.N) {
+                            if (!gate_side) L.y[at + v] = o[v];
+                            if (L.acc_debug) L.acc_debug[at + v] = a[v];
+                        }
                     }
                 }
+            }
+            if (pair && !gate_side && p.amax_out) {
+                // per token: the larger of the two lanes that hold its rows, then one atomic
+                // (non-negative floats order like their bit patterns)
+                zmax = fmaxf(zmax, __shfl_xor(zmax, 32, 64));
+                if (hf == 0 && m_ok)
+                    atomicMax(reinterpret_cast<unsigned *>(p.amax_out) + m, __builtin_bit_cast(unsigned, zmax));
             }
         }
     }
@@ -302,8 +349,13 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
     // one per tile and eight per workgroup (two per SIMD, so each keeps 256 registers)
     int kw = 1;
     while (kw < 8 && kw * 2 <= p.KT && rb_total * kw < kTargetWaves) kw *= 2;
+    if (p.pair) {
+        // a workgroup per row-block index, two sets of up to four wavefronts (gate rows, up rows)
+        if (p.G != 2 || p.L[0].N != p.L[1].N) return hipErrorInvalidValue;
+        if (kw > 4) kw = 4;
+    }
     p.KW = kw;
-    p.RW = kw >= 4 ? 1 : 4 / kw;
+    p.RW = p.pair ? 2 : (kw >= 4 ? 1 : 4 / kw);
     const int nwaves = p.RW * p.KW;
     int wgs = 0;
     for (int g = 0; g < p.G; ++g) {
@@ -311,8 +363,11 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
         wgs += (p.L[g].RBn + p.RW - 1) / p.RW;
     }
     p.wg_start[p.G] = wgs;
+    if (p.pair) wgs = p.L[0].RBn;
 
-    const size_t hbytes = (size_t)M * hstride_max * sizeof(_Float16);
+    const size_t heach = ((size_t)M * hstride_max * sizeof(_Float16) + 15) & ~size_t(15);
+    const size_t hbytes = heach * (p.pair ? 2 : 1);
+    p.h_each = (int)heach;
     const size_t gbytes = (size_t)p.RW * kTileRows * sizeof(float);
     // stretch of d_in staged in LDS: as long as fits the budget (whole rows for small M)
     int ct = (int)(((kDecodeLdsBudget - hbytes - gbytes) / M - 16) / kTileCols);
@@ -321,7 +376,9 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
     p.CT = ct;
     p.xstride = ct * kTileCols + 16;
     size_t stage = (size_t)M * p.xstride;
-    const size_t red = (size_t)(nwaves - p.RW) * tgroups * 64 * sizeof(v16i);
+    size_t red = (size_t)(nwaves - p.RW) * tgroups * 64 * sizeof(v16i);
+    p.exch_off = (int)red;                     // pair: the gate's fp32 outputs, behind the partial tiles
+    if (p.pair) red += (size_t)tgroups * 16 * 64 * sizeof(float);
     if (stage < red) stage = red;
     stage = (stage + 15) & ~size_t(15);
     p.h_off = (int)stage;

@@ -171,6 +171,7 @@ struct ProParams {
     int8_t *xq;
     float *s_x;
     int32_t *rowsum;
+    float *amax_zero;    // nullable: [M] floats the quantising workgroups set to zero (a later kernel's atomic max)
     int M, K, Kp, G;
     ProLayer L[kMaxGroup];
     int job_start[kMaxGroup + 1];
@@ -197,6 +198,12 @@ struct DecodeParams {
     int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4 or 8)
     int CT, xstride;         // tiles of d_in staged in LDS at a time; bytes per staged row
     int h_off, g_off;        // byte offsets in LDS of the SiLU(A x) rows and of the tanh(alpha) table
+    // SwiGLU pair (G == 2, both layers of one shape): a workgroup takes the SAME row-block of
+    // layer 0 (gate) and layer 1 (up), one half of its wavefronts each, and stores
+    // z = SiLU(y_gate) * y_up to L[1].y; L[0].y is unused.
+    int pair;
+    int h_each, exch_off;    // pair: bytes per layer of the SiLU(A x) rows in LDS; offset of the y_gate exchange
+    float *amax_out;         // pair, nullable: per-token max |z| (zeroed before the launch; combined with atomic max)
 };
 
 // Single persistent launch for a handful of tokens: every workgroup quantises the tokens
@@ -260,7 +267,8 @@ static_assert(sizeof(StackParams) <= 4096, "kernel arguments");
 hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_out, hipStream_t st);
 hipError_t launch_pack(const float *W, int N, int K, const float *s_w, uint32_t *packed, hipStream_t st);
 hipError_t launch_unpack(const uint32_t *packed, int N, int K, int8_t *T, hipStream_t st);
-hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st);
+hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st);   // whole 16-byte units, 16-byte aligned
+hipError_t launch_zero_words(void *p, size_t n, hipStream_t st);
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st);
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
@@ -275,7 +283,11 @@ hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);
 bool plan_stack(StackParams &p, size_t *lds_bytes);
 void set_stack_wait_limit(int tries);
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
+struct PairOut {                 // extra outputs of a SwiGLU pair launch (both nullable)
+    int32_t *acc_debug2;         // the up projection's int32 accumulators
+    float *amax_out;             // per-token max |z|
+};
 hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
-                          void *const *ys, int32_t *acc_debug, hipStream_t st);
+                          void *const *ys, int32_t *acc_debug, hipStream_t st, const PairOut *pair_out = nullptr);
 
 }  // namespace hgf

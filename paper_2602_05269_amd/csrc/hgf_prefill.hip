@@ -50,6 +50,11 @@ struct PrefillParams {
     // token tiles = xt (mod tx), nbl x mbl of them at most, row tiles first -- so an L2 holds
     // 1/rx of the weights and sees 1/tx of the activations.
     int rx, tx, nbl, mbl;
+    // SwiGLU pair (PAIR kernels): L[0] is the gate projection, L[1] the up projection, of one
+    // shape.  A wavefront takes the SAME row-block of both (a workgroup: 128 rows x 2 layers)
+    // and stores z = SiLU(y_gate) * y_up to L[1].y; neither y goes to memory.
+    int32_t *acc_debug2;           // pair: the up projection's accumulators (nullable)
+    float *amax_out;               // pair, nullable: per-token max |z| (zeroed before; atomic max)
     PrefillLayer L[kMaxGroup];
 };
 
@@ -69,7 +74,7 @@ __device__ inline unsigned piece_slot(unsigned piece, unsigned row) { return pie
 // two workgroups per compute unit cost less.  The main loop keeps the matrix core about 85 %
 // busy per clock with one workgroup in residence and 90 % with two; under either the chip's power
 // management holds the clock near 1.6 GHz.
-template <int JS, int PM>
+template <int JS, int PM, bool PAIR>
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 {
     constexpr int kPG = PM / 32;                         // token groups of 32 per wavefront
@@ -88,30 +93,43 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     const int nbg = (within % p.nbl) * p.rx + xcd % p.rx, mb = (within / p.nbl) * p.tx + xcd / p.rx;
     if (nbg >= p.NB || mb >= p.MB) return;           // padding of the arrangement
     int g = 0;
-    while (g + 1 < p.G && nbg >= p.L[g + 1].nb_start) ++g;
+    while (!PAIR && g + 1 < p.G && nbg >= p.L[g + 1].nb_start) ++g;
     const PrefillLayer &L = p.L[g];
     const int nb = nbg - L.nb_start;
-    const int rb0 = nb * (kPN / kTileRows) + w * 2;      // this wavefront's first row-block
+    // this wavefront's first row-block; its second is the next one (PAIR: the same one of layer 1)
+    const int rb0 = PAIR ? nb * (kPN / kTileRows / 2) + w : nb * (kPN / kTileRows) + w * 2;
     const int m0 = mb * PM;
     const int mrows = min(PM, p.M - m0);
 
     rsrc_t wr[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        const bool ok = rb0 + rb < L.RBn;
-        wr[rb] = make_rsrc(L.packed + (size_t)(ok ? rb0 + rb : 0) * p.KT * 64, ok ? (unsigned)p.KT * kTileBytes : 0u);
+        const int rbi = PAIR ? rb0 : rb0 + rb;
+        const bool ok = rbi < L.RBn;
+        const v4u *packed = PAIR ? p.L[rb].packed : L.packed;
+        wr[rb] = make_rsrc(packed + (size_t)(ok ? rbi : 0) * p.KT * 64, ok ? (unsigned)p.KT * kTileBytes : 0u);
     }
     const rsrc_t xr = make_rsrc(p.xq + (size_t)m0 * p.Kp, (unsigned)mrows * p.Kp);
 
-    {   // gate table
+    if (!PAIR) {   // gate table
         const rsrc_t ar = make_rsrc(L.alpha, L.rank > 0 ? (unsigned)L.N * 2u : 0u);
         const int n = nb * kPN + tid;
         const float a = (float)half_bits(buf_load2(ar, (unsigned)n * 2u, n < L.N));
         gs[tid] = L.rank > 0 ? tanhf(a) : 0.f;
+    } else {       // entry (2 w' + rb') * 32 + r: row (4 nb + w') * 32 + r of layer rb'
+        const int lay = (tid >> 5) & 1;
+        const int n = (nb * (kPN / kTileRows / 2) + (tid >> 6)) * kTileRows + (tid & 31);
+        const rsrc_t ar0 = make_rsrc(p.L[0].alpha, p.L[0].rank > 0 ? (unsigned)p.L[0].N * 2u : 0u);
+        const rsrc_t ar1 = make_rsrc(p.L[1].alpha, p.L[1].rank > 0 ? (unsigned)p.L[1].N * 2u : 0u);
+        const float a0 = (float)half_bits(buf_load2(ar0, (unsigned)n * 2u, lay == 0 && n < p.L[0].N));
+        const float a1 = (float)half_bits(buf_load2(ar1, (unsigned)n * 2u, lay == 1 && n < p.L[1].N));
+        const int rank = lay == 0 ? p.L[0].rank : p.L[1].rank;
+        gs[tid] = rank > 0 ? tanhf(lay == 0 ? a0 : a1) : 0.f;
     }
 
-    // the weight scale and the per-token scales of this lane's tokens, requested now, used in the epilogue
+    // the weight scale(s) and the per-token scales of this lane's tokens, requested now, used in the epilogue
     const float s_w = *L.s_w;
+    const float s_w2 = PAIR ? *p.L[1].s_w : s_w;
     float sx[kPG];
     int rs[kPG];
     {
@@ -268,6 +286,111 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
     // one memory round trip for the whole epilogue.
     constexpr int kRowBytes = JS * 32, kPieces = JS * 2, kMask = (kPieces < 8 ? kPieces : 8) - 1;
     constexpr unsigned kBufBytes = PM * kTileCols;
+    if constexpr (PAIR) {
+        // ---- SwiGLU pair: acc[0] holds this wavefront's row-block of the gate projection and
+        //      acc[1] the same rows of the up projection, element for element in the same
+        //      lanes, so z = SiLU(y_gate) * y_up forms in registers.  SiLU(A x) of the gate
+        //      goes to (xs0, xs1), of the up projection to (xs2, xs3); direct stores.
+        auto hplace2 = [&](int lay, unsigned byte) -> unsigned char * {
+            unsigned char *a = lay ? xs2 : xs0, *b = lay ? xs3 : xs1;
+            return byte < kBufBytes ? a + byte : b + (byte - kBufBytes);
+        };
+        v8h breg[2][JS > 0 ? JS : 1];
+        if (JS > 0) {
+#pragma unroll
+            for (int lay = 0; lay < 2; ++lay) {
+                // (a layer without correction has no rows: an empty descriptor reads zeros)
+                const rsrc_t hr = make_rsrc(p.L[lay].h16 + (size_t)m0 * p.hstride,
+                                            p.L[lay].rank > 0 ? (unsigned)mrows * p.hstride * 2u : 0u);
+#pragma unroll
+                for (int i = 0; i < PM * kRowBytes / 4096; ++i) {
+                    const unsigned byte = (unsigned)(4 * i + w) * 1024 + l * 16;
+                    const unsigned row = byte / kRowBytes, slot = (byte % kRowBytes) / 16;
+                    const unsigned piece = slot ^ (row & kMask);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(hr, (lds_ptr_t)hplace2(lay, (unsigned)(4 * i + w) * 1024), 16,
+                                                             (int)(row * (unsigned)p.hstride * 2u + piece * 16), 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int lay = 0; lay < 2; ++lay) {
+                const int rank = p.L[lay].rank;
+                const rsrc_t br = make_rsrc(p.L[lay].B, (unsigned)p.L[lay].N * rank * 2u);
+                const bool bvec = (rank % 8) == 0;
+                const int brow = rb0 * kTileRows + jl;
+                const bool ok = rank > 0 && brow < p.L[lay].N;
+#pragma unroll
+                for (int js = 0; js < JS; ++js) {
+                    const int j0 = js * 16 + hf * 8;
+                    breg[lay][js] = bvec ? buf_load8h<true>(br, (unsigned)brow * rank + j0, rank - j0, ok)
+                                         : buf_load8h<false>(br, (unsigned)brow * rank + j0, rank - j0, ok);
+                }
+            }
+            __syncthreads();         // waits for the loads above and makes the staged rows visible
+        }
+        const int N = p.L[1].N;
+        _Float16 *const z = p.L[1].y;
+        const bool nvec = (N % 4) == 0;
+        const int n0 = rb0 * kTileRows;
+#pragma unroll
+        for (int tg = 0; tg < kPG; ++tg) {
+            const int m = m0 + tg * 32 + jl;
+            const float scale_g = sx[tg] * s_w, scale_u = sx[tg] * s_w2;
+            v16f corr[2] = {(v16f){}, (v16f){}};
+            if (JS > 0) {
+                const unsigned row = (unsigned)tg * 32 + jl;
+#pragma unroll
+                for (int js = 0; js < JS; ++js) {
+                    const unsigned piece = (unsigned)(js * 2 + hf) ^ (row & kMask);
+#pragma unroll
+                    for (int lay = 0; lay < 2; ++lay) {
+                        const unsigned char *hrow = hplace2(lay, (unsigned)tg * 32 * kRowBytes) + jl * kRowBytes;
+                        const v8h b = *reinterpret_cast<const v8h *>(hrow + piece * 16);
+                        corr[lay] = __builtin_amdgcn_mfma_f32_32x32x16_f16(breg[lay][js], b, corr[lay], 0, 0, 0);
+                    }
+                }
+            }
+            float zmax = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r0 = 8 * q + 4 * hf;
+                const int nl = n0 + r0;
+                int ag[4], au[4];
+                v4h o;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    ag[v] = acc[0][tg][4 * q + v] - rs[tg];
+                    au[v] = acc[1][tg][4 * q + v] - rs[tg];
+                    const float yg = (float)ag[v] * scale_g + gs[(w * 2 + 0) * kTileRows + r0 + v] * corr[0][4 * q + v];
+                    const float yu = (float)au[v] * scale_u + gs[(w * 2 + 1) * kTileRows + r0 + v] * corr[1][4 * q + v];
+                    o[v] = (_Float16)(silu(yg) * yu);
+                    if (nl + v < N) zmax = fmaxf(zmax, fabsf((float)o[v]));
+                }
+                if (m < p.M) {
+                    const size_t at = (size_t)m * N + nl;
+                    if (nvec && nl + 3 < N) {
+                        *reinterpret_cast<v4h *>(z + at) = o;
+                        if (p.acc_debug) *reinterpret_cast<v4i *>(p.acc_debug + at) = (v4i){ag[0], ag[1], ag[2], ag[3]};
+                        if (p.acc_debug2) *reinterpret_cast<v4i *>(p.acc_debug2 + at) = (v4i){au[0], au[1], au[2], au[3]};
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            if (nl + v < N) {
+                                z[at + v] = o[v];
+                                if (p.acc_debug) p.acc_debug[at + v] = ag[v];
+                                if (p.acc_debug2) p.acc_debug2[at + v] = au[v];
+                            }
+                        }
+                    }
+                }
+            }
+            if (p.amax_out) {        // per token: the larger of its two lanes, then one atomic
+                zmax = fmaxf(zmax, __shfl_xor(zmax, 32, 64));
+                if (hf == 0 && m < p.M && n0 < N)
+                    atomicMax(reinterpret_cast<unsigned *>(p.amax_out) + m, __builtin_bit_cast(unsigned, zmax));
+            }
+        }
+        return;
+    }
     auto hplace = [&](unsigned byte) -> unsigned char * {
         return byte < kBufBytes ? xs0 + byte : (PM == 64 ? xs3 : xs1) + (byte - kBufBytes);
     };
@@ -379,8 +502,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillParams p)
 
 // Layers [0, G) read the same quantised activations (the workspace's); consecutive layers whose
 // correction paths have the same padded rank share a launch.
+// pair_out != nullptr: the SwiGLU pair (G == 2; layers[0] gate, layers[1] up): ys[1] receives
+// z = SiLU(y_gate) * y_up, ys[0] is unused.
 hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
-                          void *const *ys, int32_t *acc_debug, hipStream_t st)
+                          void *const *ys, int32_t *acc_debug, hipStream_t st, const PairOut *pair_out)
 {
     static int num_cus = 0;
     if (num_cus == 0) {
@@ -393,18 +518,25 @@ hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, cons
         num_cus = n;
     }
     auto steps_of = [](const hgf_layer &L) { return L.rank > 0 ? h_stride(L.rank) / 16 : 0; };
+    const bool pair = pair_out != nullptr;
+    if (pair && (G != 2 || layers[0].d_out != layers[1].d_out)) return hipErrorInvalidValue;
+    // pair: the two correction paths must pad to one width (a zero rank rides along with the other's)
+    const int pair_steps = pair ? (steps_of(layers[0]) > steps_of(layers[1]) ? steps_of(layers[0]) : steps_of(layers[1])) : 0;
     for (int first = 0; first < G;) {
         int n = 1;
-        while (!acc_debug && first + n < G && steps_of(layers[first + n]) == steps_of(layers[first])) ++n;
+        while (!acc_debug && !pair && first + n < G && steps_of(layers[first + n]) == steps_of(layers[first])) ++n;
+        if (pair) n = 2;
         PrefillParams p;
         p.xq = ws.xq;
         p.s_x = ws.s_x;
         p.rowsum = ws.rowsum;
         p.acc_debug = acc_debug;
+        p.acc_debug2 = pair ? pair_out->acc_debug2 : nullptr;
+        p.amax_out = pair ? pair_out->amax_out : nullptr;
         p.M = M;
         p.Kp = round_up(layers[first].d_in, kTileCols);
         p.KT = p.Kp / kTileCols;
-        p.hstride = h_stride(layers[first].rank > 0 ? layers[first].rank : 1);
+        p.hstride = pair ? (pair_steps > 0 ? pair_steps * 16 : 32) : h_stride(layers[first].rank > 0 ? layers[first].rank : 1);
         p.G = n;
         p.NB = 0;
         for (int g = 0; g < n; ++g) {
@@ -421,6 +553,10 @@ hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, cons
             P.rank = L.rank;
             P.nb_start = p.NB;
             p.NB += (L.d_out + kPN - 1) / kPN;
+        }
+        if (pair) {
+            p.L[1].nb_start = 0;
+            p.NB = (layers[0].d_out + kPN / 2 - 1) / (kPN / 2);    // a workgroup: 128 rows of both layers
         }
         for (int g = n; g < kMaxGroup; ++g) p.L[g] = p.L[0];
         // Tile width.  Two workgroups fit a compute unit, so the tiles run in rounds of
@@ -445,12 +581,17 @@ hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, cons
         p.nbl = (p.NB + p.rx - 1) / p.rx;
         p.mbl = (p.MB + p.tx - 1) / p.tx;
         const dim3 grid(8 * p.nbl * p.mbl), block(256);
-#define HGF_PREFILL(JS)                                                                        \
-    do {                                                                                       \
-        if (narrow) hipLaunchKernelGGL((prefill_kernel<JS, 64>), grid, block, 0, st, p);       \
-        else hipLaunchKernelGGL((prefill_kernel<JS, 128>), grid, block, 0, st, p);             \
+#define HGF_PREFILL(JS)                                                                              \
+    do {                                                                                             \
+        if (pair) {                                                                                  \
+            if (narrow) hipLaunchKernelGGL((prefill_kernel<JS, 64, true>), grid, block, 0, st, p);   \
+            else hipLaunchKernelGGL((prefill_kernel<JS, 128, true>), grid, block, 0, st, p);         \
+        } else {                                                                                     \
+            if (narrow) hipLaunchKernelGGL((prefill_kernel<JS, 64, false>), grid, block, 0, st, p);  \
+            else hipLaunchKernelGGL((prefill_kernel<JS, 128, false>), grid, block, 0, st, p);        \
+        }                                                                                            \
     } while (0)
-        switch (steps_of(layers[first])) {
+        switch (pair ? pair_steps : steps_of(layers[first])) {
             case 0: HGF_PREFILL(0); break;
             case 2: HGF_PREFILL(2); break;
             case 4: HGF_PREFILL(4); break;

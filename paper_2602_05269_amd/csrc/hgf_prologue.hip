@@ -98,6 +98,7 @@ __device__ void quantize_row(const ProParams &p, int m)
     if (tid == 0) {
         p.s_x[m] = amax / 127.0f;
         p.rowsum[m] = sh_sum[0] + sh_sum[1] + sh_sum[2] + sh_sum[3];
+        if (p.amax_zero) p.amax_zero[m] = 0.0f;
     }
 }
 

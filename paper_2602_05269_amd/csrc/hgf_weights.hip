@@ -119,7 +119,22 @@ __global__ __launch_bounds__(256) void fill_kernel(uint4 *__restrict__ p, size_t
     for (; i < n16; i += stride) p[i] = make_uint4(word, word, word, word);
 }
 
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *__restrict__ p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 }  // namespace
+
+// Zeroes n 4-byte words at any 4-byte aligned address (a kernel, so it may be captured in a graph).
+hipError_t launch_zero_words(void *p, size_t n, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t *>(p), n);
+    return hipGetLastError();
+}
 
 hipError_t launch_wsum(const float *W, size_t n, double *partials, float *s_w_out, hipStream_t st)
 {

@@ -303,6 +303,32 @@ def test_silu_limits_and_gate_sign():
     assert g[2] < 0 and abs(g[3] - 0.0997) < 2e-4        # fp16(0.1) is 0.09998
 
 
+def test_swiglu_against_library_silu_and_limits():
+    """z = SiLU(y_gate) * y_up against torch's silu (a library routine) in fp64, and the limits:
+    y_gate = 0 gives 0; a large y_gate passes y_up through scaled by y_gate; a very negative one
+    closes the gate.  The pair forward is the two single layers and this product."""
+    import torch
+    rng = np.random.default_rng(5)
+    yg = rng.standard_normal((7, 33)) * 3.0
+    yu = rng.standard_normal((7, 33)) * 2.0
+    z = orc.swiglu(yg, yu)
+    ref = (torch.nn.functional.silu(torch.from_numpy(yg)) * torch.from_numpy(yu)).numpy()
+    assert np.allclose(z, ref, rtol=1e-13, atol=1e-15)
+    edge = orc.swiglu(np.array([[0.0, 40.0, -40.0, 1.0]]), np.array([[5.0, 3.0, 3.0, 2.0]]))[0]
+    assert edge[0] == 0.0 and abs(edge[1] - 120.0) < 1e-12 and abs(edge[2]) < 1e-14
+    assert abs(edge[3] - 2.0 / (1.0 + math.exp(-1.0))) < 1e-15
+    a = _case(31, 5, 96, 40, 8, lora_std=0.3)
+    b = _case(32, 5, 96, 40, 16, lora_std=0.3)
+    out = orc.swiglu_pair_forward(a["x"], a, b)
+    ya = orc.linear_forward(a["x"], a["T"], a["s_w"], a["A"], a["B"], a["alpha"])["y"]
+    yb = orc.linear_forward(a["x"], b["T"], b["s_w"], b["A"], b["B"], b["alpha"])["y"]
+    assert np.allclose(out["z"], ya * expit(ya) * yb, rtol=1e-13, atol=1e-15)
+    assert out["z16"].dtype == np.float16
+    assert np.array_equal(out["amax"], np.abs(out["z"].astype(np.float16)).max(axis=1).astype(np.float32))
+    # both layers were quantised from the same activations
+    assert np.array_equal(out["gate"]["xq"], out["up"]["xq"])
+
+
 def test_stack_is_the_chain_of_fp16_rounded_layers():
     a = _case(21, 3, 64, 48, 8)
     b = _case(22, 3, 48, 32, 8)
