@@ -114,6 +114,15 @@ hgf_status hgf_unpack_weights(const void *packed, int d_out, int d_in, int8_t *T
 hgf_status hgf_quantize_activations(const void *x_f16, int M, int d_in, int8_t *xq_out,
                                     float *s_x_out, int32_t *rowsum_out, void *stream);
 
+/* The same quantiser behind a LayerNorm, fused (appendix implementation, BitLinear forward):
+ * v = ((x - mu) * rstd) * gamma + beta with mu = mean_k x and rstd = 1/sqrt(mean_k (x-mu)^2 + eps),
+ * the two reductions in fp64 rounded once to fp32, the elementwise part in fp32 in the order
+ * written; then amax, x_q, s_x and rowsum of v exactly as above.  The normalised row is never
+ * stored.  ln_gamma fp32 [d_in]; ln_beta fp32 [d_in] or NULL (zero). */
+hgf_status hgf_layernorm_quantize_activations(const void *x_f16, int M, int d_in, const float *ln_gamma,
+                                              const float *ln_beta, float ln_eps, int8_t *xq_out,
+                                              float *s_x_out, int32_t *rowsum_out, void *stream);
+
 /* ---------------------------------------------------------------- one layer */
 
 typedef struct {
@@ -125,6 +134,13 @@ typedef struct {
     const void *B_f16;      /* fp16 [d_out, rank]  up-projection                                  */
     const void *alpha_f16;  /* fp16 [d_out]        gate parameter, g = tanh(alpha)                */
     int src_slot, dst_slot; /* used only by hgf_stack_forward                                     */
+    /* Optional LayerNorm in front of the backbone's quantiser (appendix implementation, BitLinear
+     * forward: the ternary path quantises layernorm(x) while the correction path reads x itself).
+     * ln_gamma == NULL: none (Algorithm 1 as printed).  Otherwise fp32 [d_in] scale and shift
+     * (ln_beta may be NULL: zero) and the epsilon added to the variance. */
+    const float *ln_gamma;
+    const float *ln_beta;
+    float ln_eps;
 } hgf_layer;
 
 /* Algorithm 1, steps 1-8, for one layer.
@@ -136,7 +152,9 @@ typedef struct {
  *             sum_k T[n,k] x_q[m,k] of step 3 (for parity tests)
  *
  * M <= 40 runs the bandwidth-bound decode kernels (weights streamed once); larger M
- * runs the int8 MFMA prefill kernel.  Both give the same integers. */
+ * runs the int8 MFMA prefill kernel.  Both give the same integers.  A layer with ln_gamma set
+ * takes the fused LayerNorm quantiser as its prologue (one more launch than a layer without;
+ * layers with a LayerNorm of their own never share a quantisation in hgf_stack_forward). */
 hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void *y_f16,
                               int32_t *acc_debug, void *workspace, size_t workspace_bytes,
                               void *stream);

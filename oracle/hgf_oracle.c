@@ -144,3 +144,36 @@ void hgf_oracle_swiglu(const double *y_gate, const double *y_up, long M, long N,
     for (long i = 0; i < M * N; ++i)
         z[i] = (y_gate[i] / (1.0 + exp(-y_gate[i]))) * y_up[i];
 }
+
+/* LayerNorm in front of the activation quantiser (appendix implementation, BitLinear forward:
+ * the backbone quantises layernorm(x) in fp32 while the correction path reads x itself):
+ *   mu = mean_k x,  var = mean_k (x - mu)^2  (biased),  out = (x - mu) / sqrt(var + eps) * gamma + beta.
+ * The two reductions are taken in fp64 and rounded once to fp32 (mu, and 1/sqrt(var + eps));
+ * the elementwise part is fp32, one rounding per operation, in the order written above:
+ * subtract, multiply by the reciprocal deviation, multiply by gamma, add beta.  The quantiser
+ * that follows decides integers from these values, so the order is part of the definition. */
+void hgf_oracle_layernorm(const float *x, long M, long K, const float *gamma, const float *beta,
+                          float eps, float *out)
+{
+    for (long m = 0; m < M; ++m) {
+        double sum = 0.0;
+        for (long k = 0; k < K; ++k)
+            sum += (double)x[m * K + k];
+        const double mu = sum / (double)K;
+        double ss = 0.0;
+        for (long k = 0; k < K; ++k) {
+            const double d = (double)x[m * K + k] - mu;
+            ss += d * d;
+        }
+        const double var = ss / (double)K;
+        const float mu32 = (float)mu;
+        const float rstd = (float)(1.0 / sqrt(var + (double)eps));
+        for (long k = 0; k < K; ++k) {
+            float v = x[m * K + k] - mu32;
+            v = v * rstd;
+            v = v * gamma[k];
+            v = v + beta[k];
+            out[m * K + k] = v;
+        }
+    }
+}

@@ -74,9 +74,25 @@ def ternarize(W: np.ndarray) -> Tuple[np.ndarray, np.float32]:
     return T, np.float32(g.value)
 
 
-def quantize_act(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Per-token absmax int8 quantisation (Algorithm 1 steps 1-2) -> (x_q, s_x, rowsum)."""
-    assert x.dtype == np.float16, "activations are fp16 (Sec. 2.1, input tensor definition)"
+def layernorm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray, eps: float = 1e-5) -> np.ndarray:
+    """LayerNorm of fp16 activations in fp32 (appendix implementation, BitLinear forward) -> fp32 [M, K]."""
+    assert x.dtype == np.float16
+    M, K = x.shape
+    xf = np.ascontiguousarray(x.astype(np.float32))
+    g = np.ascontiguousarray(gamma, dtype=np.float32)
+    b = np.ascontiguousarray(beta, dtype=np.float32)
+    assert g.shape == (K,) and b.shape == (K,)
+    out = np.empty((M, K), dtype=np.float32)
+    _load().hgf_oracle_layernorm(_p(xf), ctypes.c_long(M), ctypes.c_long(K), _p(g), _p(b),
+                                 ctypes.c_float(float(eps)), _p(out))
+    return out
+
+
+def quantize_act(x: np.ndarray, allow_f32: bool = False) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Per-token absmax int8 quantisation (Algorithm 1 steps 1-2) -> (x_q, s_x, rowsum).
+    allow_f32: the input is the fp32 output of layernorm() rather than fp16 activations."""
+    assert x.dtype == np.float16 or (allow_f32 and x.dtype == np.float32), \
+        "activations are fp16 (Sec. 2.1, input tensor definition)"
     M, K = x.shape
     xf = np.ascontiguousarray(x.astype(np.float32))
     xq = np.empty((M, K), dtype=np.int8)
@@ -115,15 +131,20 @@ def int_gemm_dense(T: np.ndarray, xq: np.ndarray) -> np.ndarray:
 
 def linear_forward(x: np.ndarray, T: np.ndarray, s_w, A: Optional[np.ndarray],
                    B: Optional[np.ndarray], alpha: Optional[np.ndarray],
-                   dense_gemm: bool = False) -> Dict[str, np.ndarray]:
+                   dense_gemm: bool = False, ln: Optional[Tuple] = None) -> Dict[str, np.ndarray]:
     """Algorithm 1 for one layer.  Returns y (fp64), y16 (its fp16 rounding), the
     integer intermediates (x_q, s_x, rowsum, acc) and both paths (y_tern, y_corr).
-    dense_gemm: take step 3 from int_gemm_dense (full-size cases) instead of the loop."""
+    dense_gemm: take step 3 from int_gemm_dense (full-size cases) instead of the loop.
+    ln = (gamma, beta, eps): the backbone quantises layernorm(x) (the appendix
+    implementation's BitLinear); the correction path still reads x itself."""
     M, K = x.shape
     N = T.shape[0]
     r = 0 if A is None else A.shape[0]
     assert r <= MAX_RANK
-    xq, s_x, rowsum = quantize_act(x)
+    if ln is None:
+        xq, s_x, rowsum = quantize_act(x)
+    else:
+        xq, s_x, rowsum = quantize_act(layernorm(x, ln[0], ln[1], ln[2]), allow_f32=True)
     acc = int_gemm_dense(T, xq) if dense_gemm else int_gemm(T, xq)
     xf = np.ascontiguousarray(x.astype(np.float32))
     Af = None if r == 0 else np.ascontiguousarray(A.astype(np.float32))

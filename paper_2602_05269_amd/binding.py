@@ -28,7 +28,8 @@ class hgf_layer(ctypes.Structure):
     _fields_ = [("d_in", ctypes.c_int), ("d_out", ctypes.c_int), ("rank", ctypes.c_int),
                 ("W_packed", ctypes.c_void_p), ("s_w", ctypes.c_void_p),
                 ("A_f16", ctypes.c_void_p), ("B_f16", ctypes.c_void_p), ("alpha_f16", ctypes.c_void_p),
-                ("src_slot", ctypes.c_int), ("dst_slot", ctypes.c_int)]
+                ("src_slot", ctypes.c_int), ("dst_slot", ctypes.c_int),
+                ("ln_gamma", ctypes.c_void_p), ("ln_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float)]
 
 
 _lib = None
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
     L.hgf_unpack_weights.argtypes = [vp, ci, ci, vp, vp]
     L.hgf_quantize_activations.restype = ci
     L.hgf_quantize_activations.argtypes = [vp, ci, ci, vp, vp, vp, vp]
+    L.hgf_layernorm_quantize_activations.restype = ci
+    L.hgf_layernorm_quantize_activations.argtypes = [vp, ci, ci, vp, vp, ctypes.c_float, vp, vp, vp, vp]
     L.hgf_linear_forward.restype = ci
     L.hgf_linear_forward.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp, sz, vp]
     L.hgf_static_scratch_bytes.restype = sz
@@ -206,13 +209,36 @@ def hgf_quantize_activations(x: torch.Tensor, stream=None) -> Tuple[torch.Tensor
     return xq, s_x, rowsum
 
 
+def hgf_layernorm_quantize_activations(x: torch.Tensor, gamma: torch.Tensor, beta: Optional[torch.Tensor],
+                                       eps: float = 1e-5, stream=None):
+    """fp16 [M, d_in] -> (x_q, s_x, rowsum) of layernorm(x) (fp32 gamma, beta [d_in]), fused."""
+    _dev(x, torch.float16, "x")
+    _dev(gamma, torch.float32, "gamma")
+    M, d_in = x.shape
+    xq = torch.empty((M, hgf_padded_k(d_in)), dtype=torch.int8, device=x.device)
+    s_x = torch.empty(M, dtype=torch.float32, device=x.device)
+    rowsum = torch.empty(M, dtype=torch.int32, device=x.device)
+    _check(lib().hgf_layernorm_quantize_activations(x.data_ptr(), M, d_in, gamma.data_ptr(), _ptr(beta), float(eps),
+                                                    xq.data_ptr(), s_x.data_ptr(), rowsum.data_ptr(), _stream(stream)),
+           "hgf_layernorm_quantize_activations")
+    return xq, s_x, rowsum
+
+
 class Layer:
     """Device tensors of one HGF linear plus the hgf_layer record that points at them."""
 
     def __init__(self, packed: torch.Tensor, s_w: torch.Tensor, d_out: int, d_in: int,
                  A: Optional[torch.Tensor] = None, B: Optional[torch.Tensor] = None,
-                 alpha: Optional[torch.Tensor] = None, src_slot: int = 0, dst_slot: int = 1):
+                 alpha: Optional[torch.Tensor] = None, src_slot: int = 0, dst_slot: int = 1,
+                 ln_gamma: Optional[torch.Tensor] = None, ln_beta: Optional[torch.Tensor] = None,
+                 ln_eps: float = 1e-5):
         self.packed, self.s_w, self.A, self.B, self.alpha = packed, s_w, A, B, alpha
+        self.ln_gamma, self.ln_beta = ln_gamma, ln_beta
+        for t, name in ((ln_gamma, "ln_gamma"), (ln_beta, "ln_beta")):
+            if t is not None:
+                _dev(t, torch.float32, name)
+                if tuple(t.shape) != (d_in,):
+                    raise ValueError(f"{name} must be [d_in]")
         rank = 0 if A is None else A.shape[0]
         if rank:
             _dev(A, torch.float16, "A"), _dev(B, torch.float16, "B"), _dev(alpha, torch.float16, "alpha")
@@ -222,7 +248,7 @@ class Layer:
             raise ValueError("packed buffer has the wrong size for these dimensions")
         self.d_in, self.d_out, self.rank = d_in, d_out, rank
         self.c = hgf_layer(d_in, d_out, rank, packed.data_ptr(), s_w.data_ptr(), _ptr(A), _ptr(B), _ptr(alpha),
-                           src_slot, dst_slot)
+                           src_slot, dst_slot, _ptr(ln_gamma), _ptr(ln_beta), float(ln_eps))
 
     @classmethod
     def from_latent(cls, W: torch.Tensor, A, B, alpha, ws: Workspace, **kw) -> "Layer":

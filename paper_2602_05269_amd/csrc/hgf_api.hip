@@ -55,6 +55,7 @@ hgf_status check_layer(const hgf_layer *L, int M)
     if (!L->W_packed || !L->s_w) return HGF_ERR_NULL;
     if (L->rank > 0 && (!L->A_f16 || !L->B_f16 || !L->alpha_f16)) return HGF_ERR_NULL;
     if (!aligned16(L->W_packed)) return HGF_ERR_ALIGN;
+    if (L->ln_gamma && !(L->ln_eps >= 0.0f)) return HGF_ERR_SHAPE;
     return HGF_OK;
 }
 
@@ -110,7 +111,8 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
                             float *amax_out = nullptr, int32_t *acc_debug2 = nullptr)
 {
     const int K = layers[0].d_in;
-    bool fused = !pair && g_launch_level >= 1 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
+    const bool ln = layers[0].ln_gamma != nullptr;   // (such a layer is always a group of its own)
+    bool fused = !pair && !ln && g_launch_level >= 1 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && aligned16(x);
     for (int g = 0; g < G; ++g)
         fused = fused && (layers[g].rank == 0 ||
                           (layers[g].rank % 8 == 0 && aligned16(layers[g].A_f16) && aligned16(layers[g].B_f16) &&
@@ -151,6 +153,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     pp.s_x = ws.s_x;
     pp.rowsum = ws.rowsum;
     pp.amax_zero = pair ? amax_out : nullptr;
+    pp.quantize = ln ? 0 : 1;
     pp.M = M;
     pp.K = K;
     pp.Kp = round_up(K, kTileCols);
@@ -185,6 +188,9 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
     }
     _Float16 *h16[kMaxGroup];
     for (int g = 0; g < G; ++g) h16[g] = const_cast<_Float16 *>(dp.L[g].h16);
+    if (ln && launch_ln_quantize(pp.x, M, K, layers[0].ln_gamma, layers[0].ln_beta, layers[0].ln_eps, ws.xq, ws.s_x,
+                                 ws.rowsum, st) != hipSuccess)
+        return HGF_ERR_DEVICE;
     if (launch_prologue(pp, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
     ProfileScope prof(0, st);
     return from_hip(launch_decode(dp, K, st));
@@ -209,7 +215,12 @@ hgf_status run_large_group(const void *x, int M, const hgf_layer *layers, int G,
     if (pair_out && pair_out->amax_out &&
         launch_zero_words(pair_out->amax_out, (size_t)M, st) != hipSuccess)
         return HGF_ERR_DEVICE;
-    if (launch_corr_down(xh, M, K, G, A, rank, h16, ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess) return HGF_ERR_DEVICE;
+    const bool ln = layers[0].ln_gamma != nullptr;   // (such a layer is always a group of its own)
+    if (ln && launch_ln_quantize(xh, M, K, layers[0].ln_gamma, layers[0].ln_beta, layers[0].ln_eps, ws.xq, ws.s_x,
+                                 ws.rowsum, st) != hipSuccess)
+        return HGF_ERR_DEVICE;
+    if (launch_corr_down(xh, M, K, G, A, rank, h16, ln ? nullptr : ws.xq, ws.s_x, ws.rowsum, st) != hipSuccess)
+        return HGF_ERR_DEVICE;
     ProfileScope prof(1, st);
     return from_hip(launch_prefill(ws, h16, M, layers, G, ys, acc_debug, st, pair_out));
 }
@@ -345,6 +356,17 @@ hgf_status hgf_quantize_activations(const void *x_f16, int M, int d_in, int8_t *
                                     reinterpret_cast<hipStream_t>(stream)));
 }
 
+hgf_status hgf_layernorm_quantize_activations(const void *x_f16, int M, int d_in, const float *ln_gamma,
+                                              const float *ln_beta, float ln_eps, int8_t *xq_out, float *s_x_out,
+                                              int32_t *rowsum_out, void *stream)
+{
+    if (!x_f16 || !xq_out || !s_x_out || !ln_gamma) return HGF_ERR_NULL;
+    if (!dims_ok(d_in, 1) || !tokens_ok(M, d_in, 1) || !(ln_eps >= 0.0f)) return HGF_ERR_SHAPE;
+    if (!aligned16(x_f16) || !aligned16(xq_out)) return HGF_ERR_ALIGN;
+    return from_hip(launch_ln_quantize(reinterpret_cast<const _Float16 *>(x_f16), M, d_in, ln_gamma, ln_beta, ln_eps,
+                                       xq_out, s_x_out, rowsum_out, reinterpret_cast<hipStream_t>(stream)));
+}
+
 hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void *y_f16, int32_t *acc_debug,
                               void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -374,6 +396,7 @@ hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, c
     if (s == HGF_OK) s = check_layer(up, M);
     if (s != HGF_OK) return s;
     if (gate->d_in != up->d_in || gate->d_out != up->d_out) return HGF_ERR_SHAPE;
+    if (gate->ln_gamma || up->ln_gamma) return HGF_ERR_UNSUPPORTED;   // (each would need a quantisation of its own)
     if (!aligned16(x_f16) || !aligned16(z_f16) || (acc_debug_gate && !aligned16(acc_debug_gate)) ||
         (acc_debug_up && !aligned16(acc_debug_up)) || (reinterpret_cast<uintptr_t>(amax_out) & 3u))
         return HGF_ERR_ALIGN;
@@ -457,13 +480,13 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
         int G = 1;
         while (i + G < n_layers && G < kMaxGroup) {
             const hgf_layer &C = layers[i + G];
-            bool ok = C.src_slot == layers[i].src_slot && C.d_in == layers[i].d_in;
+            bool ok = C.src_slot == layers[i].src_slot && C.d_in == layers[i].d_in && !C.ln_gamma && !layers[i].ln_gamma;
             for (int j = i; ok && j < i + G; ++j) ok = layers[j].dst_slot != C.dst_slot;
             if (!ok) break;
             ++G;
         }
         const int K = layers[i].d_in;
-        bool stackable = g_launch_level >= 2 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK;
+        bool stackable = g_launch_level >= 2 && M <= kMaxFusedM && K % 8 == 0 && K <= kMaxFusedK && !layers[i].ln_gamma;
         for (int g = 0; g < G && stackable; ++g) {
             const hgf_layer &L = layers[i + g];
             stackable = L.d_out % 8 == 0 &&

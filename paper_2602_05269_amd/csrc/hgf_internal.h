@@ -172,6 +172,7 @@ struct ProParams {
     float *s_x;
     int32_t *rowsum;
     float *amax_zero;    // nullable: [M] floats the quantising workgroups set to zero (a later kernel's atomic max)
+    int quantize;        // 0: x_q, s_x and the row sums are already there (the LayerNorm quantiser wrote them)
     int M, K, Kp, G;
     ProLayer L[kMaxGroup];
     int job_start[kMaxGroup + 1];
@@ -271,6 +272,8 @@ hipError_t launch_fill(void *p, size_t bytes, uint32_t word, hipStream_t st);   
 hipError_t launch_zero_words(void *p, size_t n, hipStream_t st);
 hipError_t launch_quantize(const _Float16 *x, int M, int K, int8_t *xq, float *s_x, int32_t *rowsum,
                            hipStream_t st);
+hipError_t launch_ln_quantize(const _Float16 *x, int M, int K, const float *gamma, const float *beta, float eps,
+                              int8_t *xq, float *s_x, int32_t *rowsum, hipStream_t st);
 hipError_t launch_corr_down(const _Float16 *x, int M, int K, int G, const _Float16 *const *A, const int *rank,
                             _Float16 *const *h16, int8_t *xq, float *s_x, int32_t *rowsum, hipStream_t st);
 int prologue_slices(int M, int K);

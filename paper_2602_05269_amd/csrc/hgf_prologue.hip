@@ -167,11 +167,12 @@ __device__ void corr_partial(const ProParams &p, int job)
 template <int TT, bool VEC>
 __global__ __launch_bounds__(256) void prologue_kernel(ProParams p)
 {
-    if ((int)blockIdx.x < p.M) {
+    const int qb = p.quantize ? p.M : 0;            // workgroups that quantise a token each
+    if ((int)blockIdx.x < qb) {
         quantize_row<VEC>(p, blockIdx.x);
         return;
     }
-    const int job = ((int)blockIdx.x - p.M) * 4 + (threadIdx.x >> 6);
+    const int job = ((int)blockIdx.x - qb) * 4 + (threadIdx.x >> 6);
     if (job < p.job_start[p.G]) corr_partial<TT, VEC>(p, job);
 }
 
@@ -234,7 +235,8 @@ hipError_t launch_prologue(ProParams &p, _Float16 *const *h16, hipStream_t st)
     }
     p.job_start[p.G] = jobs;
     const bool vec = (p.K % 8 == 0) && aligned;
-    const dim3 grid(p.M + (jobs + 3) / 4), block(256);
+    const dim3 grid((p.quantize ? p.M : 0) + (jobs + 3) / 4), block(256);
+    if (grid.x == 0) return hipSuccess;             // nothing to quantise, no correction path
     const int tt = (p.M + 15) / 16;
 #define HGF_PRO(TT_)                                                                        \
     if (vec) hipLaunchKernelGGL((prologue_kernel<TT_, true>), grid, block, 0, st, p);       \

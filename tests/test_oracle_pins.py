@@ -329,6 +329,59 @@ def test_swiglu_against_library_silu_and_limits():
     assert np.array_equal(out["gate"]["xq"], out["up"]["xq"])
 
 
+def test_layernorm_against_library_and_special_cases():
+    """The LayerNorm in front of the quantiser against torch's layer_norm in fp64 (a library
+    routine), and what the definition fixes: zero mean and unit variance of the un-scaled
+    output, a constant row mapping to beta exactly, rows normalised independently."""
+    import torch
+    rng = np.random.default_rng(9)
+    M, K = 6, 333
+    x = (rng.standard_normal((M, K)) * 3.0 + 1.5).astype(np.float16)
+    gamma = (1.0 + 0.2 * rng.standard_normal(K)).astype(np.float32)
+    beta = (0.3 * rng.standard_normal(K)).astype(np.float32)
+    out = orc.layernorm(x, gamma, beta, 1e-5)
+    assert out.dtype == np.float32
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x.astype(np.float64)), (K,),
+                                         torch.from_numpy(gamma.astype(np.float64)),
+                                         torch.from_numpy(beta.astype(np.float64)), 1e-5).numpy()
+    assert np.allclose(out, ref, rtol=2e-6, atol=2e-6)
+    plain = orc.layernorm(x, np.ones(K, np.float32), np.zeros(K, np.float32), 1e-5).astype(np.float64)
+    assert np.abs(plain.mean(axis=1)).max() < 1e-6 and np.abs(plain.var(axis=1) - 1.0).max() < 1e-4
+    const = np.full((1, K), 2.5, dtype=np.float16)
+    assert np.array_equal(orc.layernorm(const, gamma, beta, 1e-5)[0], beta)
+    x2 = x.copy()
+    x2[3] = x2[3] * np.float16(2.0) + np.float16(1.0)
+    out2 = orc.layernorm(x2, gamma, beta, 1e-5)
+    keep = [i for i in range(M) if i != 3]
+    assert np.array_equal(out2[keep], out[keep])
+    # a shifted and scaled row normalises to (nearly) the same values: eps is all that differs
+    assert np.allclose(out2[3], out[3], rtol=0, atol=5e-3)
+
+
+def test_layer_with_layernorm_quantises_the_normalised_input_only():
+    """With ln set, the backbone contracts Q(layernorm(x)) (checked against numpy's own LayerNorm
+    inside the quantiser's error bound of half a step) while the correction path still reads x:
+    y_corr is unchanged, y_tern is the dense product of the de-quantised normalised input."""
+    c = _case(41, 5, 200, 48, 8, act="student_t3", lora_std=0.3)
+    rng = np.random.default_rng(41)
+    gamma = (1.0 + 0.3 * rng.standard_normal(200)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(200)).astype(np.float32)
+    base = orc.linear_forward(c["x"], c["T"], c["s_w"], c["A"], c["B"], c["alpha"])
+    out = orc.linear_forward(c["x"], c["T"], c["s_w"], c["A"], c["B"], c["alpha"], ln=(gamma, beta, 1e-5))
+    assert np.array_equal(out["y_corr"], base["y_corr"])
+    assert not np.array_equal(out["xq"], base["xq"])
+    xf = c["x"].astype(np.float64)
+    mu, var = xf.mean(axis=1, keepdims=True), xf.var(axis=1, keepdims=True)
+    v = (xf - mu) / np.sqrt(var + 1e-5) * gamma.astype(np.float64) + beta.astype(np.float64)
+    s_x = out["s_x"].astype(np.float64)[:, None]
+    assert np.allclose(s_x[:, 0] * 127.0, np.abs(v).max(axis=1), rtol=1e-5)
+    assert (np.abs(v - out["xq"].astype(np.float64) * s_x) <= 0.5 * s_x * (1 + 1e-3) + 1e-5).all()
+    w_hat = c["T"].astype(np.float64) * float(c["s_w"])
+    assert np.allclose(out["y_tern"], (out["xq"].astype(np.float64) * s_x) @ w_hat.T, rtol=1e-12, atol=1e-14)
+    assert np.allclose(out["y"], out["y_tern"] + np.tanh(c["alpha"].astype(np.float64))[None, :] * out["y_corr"],
+                       rtol=1e-13, atol=1e-15)
+
+
 def test_stack_is_the_chain_of_fp16_rounded_layers():
     a = _case(21, 3, 64, 48, 8)
     b = _case(22, 3, 48, 32, 8)
