@@ -83,11 +83,30 @@ class Workload:
                 slots[src] = torch.from_numpy(synth.make_activations(cfg, 0, proj, M)).cuda()
             slots[dst] = torch.zeros((M, p.d_out), dtype=torch.float16, device="cuda")
             self.shapes.append((p.d_in, p.d_out, c.rank))
+        self.wiring, self.proj_of = wiring, [w[1] for w in wiring]
+        self._finish(slots, M)
+
+    def _finish(self, slots, M):
+        self.M, self.slots = M, slots
         self.stack = hb.Stack(self.layers, slots, M)
         self.bytes = sum(linear_bytes(K, N, r, M) for K, N, r in self.shapes)
         self.main_bytes = sum(main_kernel_bytes(K, N, r, M) for K, N, r in self.shapes)
         self.int8_ops = sum(2.0 * M * K * N for K, N, _ in self.shapes)
         self.param_bytes = sum(K * N / 4 + 2 * r * (K + N) + 2 * N + 4 for K, N, r in self.shapes)
+
+    def with_tokens(self, M: int) -> "Workload":
+        """The same weights and wiring at another number of tokens (fresh input and slots)."""
+        import copy
+        other = copy.copy(self)
+        c = synth.CONFIGS[self.cfg]
+        slots = [None] * len(self.slots)
+        slots[0] = torch.from_numpy(synth.make_activations(self.cfg, 0, self.wiring[0][1], M)).cuda()
+        for (_layer, proj, src, dst) in self.wiring:
+            if slots[src] is None:
+                slots[src] = torch.from_numpy(synth.make_activations(self.cfg, 0, proj, M)).cuda()
+            slots[dst] = torch.zeros((M, c.projections[proj].d_out), dtype=torch.float16, device="cuda")
+        other._finish(slots, M)
+        return other
 
 
 def time_steps(fn, steps: int, warmup: int, events: bool = False):
@@ -217,6 +236,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--blocks", type=int, default=32, help="distinct weight instances (FFN blocks) per step")
+    ap.add_argument("--tokens", type=int, default=1,
+                    help="tokens M of the primary workload (default 1, the headline metric; other values are "
+                         "for profiling the few-token paths)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-secondary", action="store_true", help="skip the secondary cases")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -247,7 +269,7 @@ def main() -> int:
     ws = hb.Workspace(2048, 11008, 11008, 128)
 
     # ---- primary: 7B-shape FFN decode, M = 1, distinct weights every block (HBM-cold)
-    wl = Workload(4, 1, args.blocks, seed=4000, ws=ws)
+    wl = Workload(4, args.tokens, args.blocks, seed=4000, ws=ws)
     run = make_runner(wl, ws, use_graph)
     sec, ev_sec = time_steps(run, args.steps, args.warmup, events=True)
     gbs = wl.bytes / sec / 1e9
@@ -265,7 +287,7 @@ def main() -> int:
     achieved = k_bytes / avg_kernel_s / 1e9
 
     out = {
-        "metric": "HGF linear achieved HBM GB/s at M=1 (7B-shape FFN decode)",
+        "metric": f"HGF linear achieved HBM GB/s at M={args.tokens} (7B-shape FFN decode)",
         "value": round(gbs, 1),
         "unit": "GB/s",
         "n_gpus": 1,
@@ -280,8 +302,10 @@ def main() -> int:
         "tokens_per_s": round(1.0 / sec, 1),
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "config": {
-            "workload": f"config 4 (7B-shape): up, gate 4096->11008 and down 11008->4096, r=128, M=1, "
-                        f"{args.blocks} chained blocks of distinct weights via hgf_stack_forward",
+            "workload": f"config 4 (7B-shape): up, gate 4096->11008 and down 11008->4096, r=128, M={args.tokens}, "
+                        f"{args.blocks} chained blocks of distinct weights via hgf_stack_forward (a pure chain of "
+                        f"linears: no norms or residuals, so the values drift block by block -- see chain_end; "
+                        f"the kernels' time does not depend on the values)",
             "linears_per_step": len(wl.layers),
             "algorithmic_bytes_per_step": int(wl.bytes),
             "launch": "hip-graph replay" if use_graph else "eager",
@@ -302,21 +326,83 @@ def main() -> int:
     }
 
     if not args.no_cpu:
-        cb = cpu_baseline(4, 1, 3, args.cpu_seconds)
+        cb = cpu_baseline(4, args.tokens, 3, args.cpu_seconds)
         out["cpu_baseline"] = {
             "value": round(cb["bytes"] / cb["seconds_per_pass"] / 1e9, 3),
             "unit": "GB/s",
             "cores": cb["cores"],
             "kind": "oracle",
-            "sample": f"one block (up, gate, down) of the workload at M=1, {cb['passes']} passes in "
+            "sample": f"one block (up, gate, down) of the workload at M={args.tokens}, {cb['passes']} passes in "
                       f"{cb['passes'] * cb['seconds_per_pass']:.1f} s; a {args.blocks}-block step would take "
                       f"{cb['seconds_per_pass'] * args.blocks * 1e3:.0f} ms",
         }
 
-    if not args.no_secondary:
+    if not args.no_secondary and args.tokens == 1:
         cases = {}
+        hbm = lambda nbytes, s_: {"us": round(s_ * 1e6, 2), "algorithmic_bytes": int(nbytes),
+                                  "GB_per_s": round(nbytes / s_ / 1e9, 1),
+                                  "frac_of_hbm_peak": round(nbytes / s_ / 1e9 / HBM_PEAK_GBS, 4)}
+        few = max(5, args.steps // 5)
+        # what the chain's values have become at its end (no norms or residuals between the linears)
+        last = wl.slots[wl.wiring[-1][3]].float()
+        out["config"]["chain_end"] = {"absmax": float(last.abs().nan_to_num(nan=0.0, posinf=65504.0).max()),
+                                      "non_finite": int((~torch.isfinite(last)).sum())}
+        # ---- config 4 at more tokens: the same 32 blocks of weights (cold), per FFN block
+        cases["config4_block_M1_cold"] = hbm(wl.bytes / args.blocks, sec / args.blocks)
+        for M in (8, 32, 64):
+            wm = wl.with_tokens(M)
+            sm = time_steps(make_runner(wm, ws, use_graph), few, 2)
+            c = hbm(wm.bytes / args.blocks, sm / args.blocks)
+            c["path"] = "two-launch decode (prologue, slice reduction, decode_kernel)" if M <= 40 else \
+                        "prefill path (prepare_kernel, prefill_kernel)"
+            cases[f"config4_block_M{M}_cold"] = c
+            del wm
+
+        # ---- the fused SwiGLU pair (gate and up of one input -> z) on the same weights, against
+        #      the two layers as one group with two outputs
+        def pair_time(M, fused):
+            x = torch.from_numpy(synth.make_activations(4, 0, 0, M)).cuda()
+            ups = [l for l, p_ in zip(wl.layers, wl.proj_of) if p_ == 0]
+            gates = [l for l, p_ in zip(wl.layers, wl.proj_of) if p_ == 1]
+            z = torch.zeros((M, ups[0].d_out), dtype=torch.float16, device="cuda")
+            z2 = torch.zeros_like(z)
+            stacks = []
+            for u, g in zip(ups, gates):
+                a = hb.Layer(u.packed, u.s_w, u.d_out, u.d_in, u.A, u.B, u.alpha, src_slot=0, dst_slot=1)
+                b = hb.Layer(g.packed, g.s_w, g.d_out, g.d_in, g.A, g.B, g.alpha, src_slot=0, dst_slot=2)
+                stacks.append(hb.Stack([a, b], [x, z, z2], M))
+
+            def step():
+                for u, g, st in zip(ups, gates, stacks):
+                    if fused:
+                        hb.hgf_swiglu_forward(x, g, u, ws, z=z)
+                    else:
+                        hb.hgf_stack_forward(st, ws)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+            torch.cuda.synchronize()
+            t = time_steps(graph.replay, few, 2) / len(ups)
+            K, N, r = ups[0].d_in, ups[0].d_out, ups[0].rank
+            nbytes = 2 * linear_bytes(K, N, r, M) - 2 * M * K - (2 * M * N if fused else 0)
+            return hbm(nbytes, t)
+        for M in (1, 8, 64):
+            cases[f"config4_swiglu_pair_M{M}_cold"] = pair_time(M, True)
+            cases[f"config4_up_gate_group_M{M}_cold"] = pair_time(M, False)
         del run, wl
         torch.cuda.empty_cache()
+        # ---- config 0: the single 256x256 linear at 8 tokens (cache-resident, launch bound)
+        w0 = Workload(0, 8, 1, seed=0, ws=ws)
+        s0 = time_steps(make_runner(w0, ws, use_graph), max(20, args.steps), args.warmup)
+        cases["config0_single_M8_hot"] = hbm(w0.bytes, s0)
+        cases["config0_single_M8_hot"]["note"] = "0.03 MB of parameters: the latency of three launches, not bandwidth"
+        del w0
         # 8-layer d=512 stack at M=1: 14.7 MB of parameters, cache-resident ("hot"), launch bound
         w1 = Workload(1, 1, 8, seed=1000, ws=ws)
         s1 = time_steps(make_runner(w1, ws, use_graph), max(10, args.steps), args.warmup)
@@ -324,13 +410,13 @@ def main() -> int:
                                          "linears": len(w1.layers),
                                          "GB_per_s_cache_resident": round(w1.bytes / s1 / 1e9, 1)}
         del w1
-        # 1.2B-shape layer, M=1, 16 distinct blocks of 7 projections (cold)
+        # 1.2B-shape layer, 16 distinct blocks of 7 projections (cold), per block
         w2 = Workload(2, 1, 16, seed=2000, ws=ws)
-        s2 = time_steps(make_runner(w2, ws, use_graph), max(10, args.steps // 2), args.warmup)
-        cases["config2_layer_M1_cold"] = {"GB_per_s": round(w2.bytes / s2 / 1e9, 1),
-                                          "frac_of_hbm_peak": round(w2.bytes / s2 / 1e9 / HBM_PEAK_GBS, 4),
-                                          "us_per_layer": round(s2 / 16 * 1e6, 2)}
-        del w2
+        for M in (1, 4, 16):
+            wm = w2 if M == 1 else w2.with_tokens(M)
+            s2 = time_steps(make_runner(wm, ws, use_graph), max(10, args.steps // 2), args.warmup)
+            cases[f"config2_layer_M{M}_cold"] = hbm(wm.bytes / 16, s2 / 16)
+        del w2, wm
         torch.cuda.empty_cache()
         # 3B-shape prefill layer, M=2048, the 7 projections of one block
         w3 = Workload(3, 2048, 1, seed=3000, ws=ws)
@@ -341,6 +427,16 @@ def main() -> int:
         cases["config3_prefill_M2048"] = {"int8_TOPS": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4),
                                           "ms_per_layer": round(s3 * 1e3, 3),
                                           "main_kernel_int8_TOPS": round(k_tops, 1)}
+        # the same block's gate and up projections as the fused SwiGLU pair (one output)
+        names = [p_.name for p_ in synth.CONFIGS[3].projections]
+        gi, ui = names.index("gate"), names.index("up")
+        xg = w3.slots[w3.wiring[ui][2]]
+        zz = torch.zeros((2048, w3.layers[ui].d_out), dtype=torch.float16, device="cuda")
+        sp = time_steps(lambda: hb.hgf_swiglu_forward(xg, w3.layers[gi], w3.layers[ui], ws, z=zz), 20, 3)
+        ops = 2 * 2.0 * 2048 * w3.layers[ui].d_in * w3.layers[ui].d_out
+        cases["config3_swiglu_pair_M2048"] = {"int8_TOPS": round(ops / sp / 1e12, 1),
+                                              "frac_of_int8_peak": round(ops / sp / 1e12 / INT8_PEAK_TOPS, 4),
+                                              "us": round(sp * 1e6, 1)}
         out["cases"] = cases
 
     print(json.dumps(out))
