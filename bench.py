@@ -397,6 +397,52 @@ def main() -> int:
             cases[f"config4_up_gate_group_M{M}_cold"] = pair_time(M, False)
         del run, wl
         torch.cuda.empty_cache()
+
+        # ---- base-3 packing (1.6 bits per weight) against the 2-bit layout: 16 distinct `up`
+        #      layers (4096 -> 11008, r=128) at M=1, one call per layer.  "same_path": the 2-bit
+        #      layer through the same three launches (prologue, slice reduction, main kernel).
+        def b3_cases():
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(4500)
+            K, N, r, nl = 4096, 11008, 128, 16
+            l2, l3 = [], []
+            for _ in range(nl):
+                W = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+                A = (torch.randn((r, K), generator=gen, device="cuda") * 0.02).half()
+                B = (torch.randn((N, r), generator=gen, device="cuda") * 0.02).half()
+                alpha = torch.randn(N, generator=gen, device="cuda").half()
+                l2.append(hb.Layer.from_latent(W, A, B, alpha, ws))
+                p3, s3 = hb.hgf_quantize_pack_weights_b3(W, ws)
+                l3.append(hb.Layer(p3, s3, N, K, A, B, alpha))
+                del W
+            x = torch.from_numpy(synth.make_activations(4, 0, 0, 1)).cuda()
+            y = torch.zeros((1, N), dtype=torch.float16, device="cuda")
+
+            def timed(fn):
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    fn()
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    fn()
+                torch.cuda.synchronize()
+                return time_steps(graph.replay, few, 2) / nl
+            res = {}
+            b2 = linear_bytes(K, N, r, 1)
+            b3 = b2 - K * N / 4 + hb.hgf_packed_weight_bytes_b3(N, K)
+            res["config4_up_M1_2bit_cold"] = hbm(b2, timed(lambda: [hb.hgf_linear_forward(x, l, ws, y=y) for l in l2]))
+            hb.hgf_set_single_launch(0)
+            try:
+                res["config4_up_M1_2bit_same_path_cold"] = hbm(b2, timed(lambda: [hb.hgf_linear_forward(x, l, ws, y=y) for l in l2]))
+            finally:
+                hb.hgf_set_single_launch(2)
+            res["config4_up_M1_base3_cold"] = hbm(b3, timed(lambda: [hb.hgf_linear_forward_b3(x, l, ws, y=y) for l in l3]))
+            return res
+        cases.update(b3_cases())
+        torch.cuda.empty_cache()
         # ---- config 0: the single 256x256 linear at 8 tokens (cache-resident, launch bound)
         w0 = Workload(0, 8, 1, seed=0, ws=ws)
         s0 = time_steps(make_runner(w0, ws, use_graph), max(20, args.steps), args.warmup)

@@ -184,6 +184,29 @@ hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, c
                               int32_t *acc_debug_up, void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* ---------------------------------------------------------------- base-3 packing (1.6 bits per weight)
+ *
+ * The paper counts its backbone at log2 3 = 1.58 bits per weight (Sec. 4.1, Def. "Effective
+ * Bit-Width").  This alternative layout stores five ternary weights per byte (3^5 = 243 <= 256):
+ * 20 % fewer bytes to stream than the 2-bit layout, for the few-token decode where the weights are
+ * nearly all the traffic.  Same ternarisation as hgf_quantize_pack_weights (same s_w, same T).
+ *
+ * Layout: row n of the matrix is ceil(d_in / 5) bytes padded to a multiple of 16 (rows start
+ * 16-byte aligned; a lane's 16-byte load is 80 weights of one row); byte g of a row is
+ * sum_{i<5} (T[n, 5g+i] + 1) * 3^i, columns past d_in counting as T = 0 (padding bytes: 121).
+ *
+ * hgf_linear_forward_b3 is Algorithm 1 for one layer whose W_packed is such a buffer, for
+ * M <= 4 tokens and d_in <= 20480 (HGF_ERR_UNSUPPORTED beyond; layers with ln_gamma likewise):
+ * the same integers as hgf_linear_forward, outputs within the same tolerance. */
+size_t hgf_packed_weight_bytes_b3(int d_out, int d_in);
+hgf_status hgf_quantize_pack_weights_b3(const float *W, int d_out, int d_in, void *packed_out,
+                                        float *s_w_out, void *workspace, size_t workspace_bytes,
+                                        void *stream);
+hgf_status hgf_unpack_weights_b3(const void *packed, int d_out, int d_in, int8_t *T_out, void *stream);
+hgf_status hgf_linear_forward_b3(const void *x_f16, int M, const hgf_layer *L, void *y_f16,
+                                 int32_t *acc_debug, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
 /* hgf_linear_forward for callers that cannot allocate device memory and have no workspace to
  * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, same kernels and same results as hgf_linear_forward, but what the workspace

@@ -72,6 +72,14 @@ def lib() -> ctypes.CDLL:
     L.hgf_static_scratch_needed.argtypes = [ci, ci, ci, ci]
     L.hgf_linear_forward_static.restype = ci
     L.hgf_linear_forward_static.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp]
+    L.hgf_packed_weight_bytes_b3.restype = sz
+    L.hgf_packed_weight_bytes_b3.argtypes = [ci, ci]
+    L.hgf_quantize_pack_weights_b3.restype = ci
+    L.hgf_quantize_pack_weights_b3.argtypes = [vp, ci, ci, vp, vp, vp, sz, vp]
+    L.hgf_unpack_weights_b3.restype = ci
+    L.hgf_unpack_weights_b3.argtypes = [vp, ci, ci, vp, vp]
+    L.hgf_linear_forward_b3.restype = ci
+    L.hgf_linear_forward_b3.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp, sz, vp]
     L.hgf_swiglu_forward.restype = ci
     L.hgf_swiglu_forward.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), ctypes.POINTER(hgf_layer), vp, vp, vp, vp, vp, sz, vp]
     L.hgf_stack_forward.restype = ci
@@ -244,7 +252,7 @@ class Layer:
             _dev(A, torch.float16, "A"), _dev(B, torch.float16, "B"), _dev(alpha, torch.float16, "alpha")
             if tuple(A.shape) != (rank, d_in) or tuple(B.shape) != (d_out, rank) or tuple(alpha.shape) != (d_out,):
                 raise ValueError("A must be [rank, d_in], B [d_out, rank], alpha [d_out]")
-        if packed.numel() != hgf_packed_weight_bytes(d_out, d_in):
+        if packed.numel() not in (hgf_packed_weight_bytes(d_out, d_in), hgf_packed_weight_bytes_b3(d_out, d_in)):
             raise ValueError("packed buffer has the wrong size for these dimensions")
         self.d_in, self.d_out, self.rank = d_in, d_out, rank
         self.c = hgf_layer(d_in, d_out, rank, packed.data_ptr(), s_w.data_ptr(), _ptr(A), _ptr(B), _ptr(alpha),
@@ -286,6 +294,43 @@ def hgf_swiglu_forward(x: torch.Tensor, gate: Layer, up: Layer, ws: Workspace, z
                                     _ptr(amax), _ptr(acc_debug_gate), _ptr(acc_debug_up), ws.buf.data_ptr(),
                                     ws.bytes, _stream(stream)), "hgf_swiglu_forward")
     return z
+
+
+def hgf_packed_weight_bytes_b3(d_out: int, d_in: int) -> int:
+    return lib().hgf_packed_weight_bytes_b3(d_out, d_in)
+
+
+def hgf_quantize_pack_weights_b3(W: torch.Tensor, ws: Workspace, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp32 [d_out, d_in] -> (base-3 packed uint8 buffer, five weights per byte; s_w fp32 scalar tensor)."""
+    _dev(W, torch.float32, "W")
+    d_out, d_in = W.shape
+    packed = torch.empty(hgf_packed_weight_bytes_b3(d_out, d_in), dtype=torch.uint8, device=W.device)
+    s_w = torch.empty(1, dtype=torch.float32, device=W.device)
+    _check(lib().hgf_quantize_pack_weights_b3(W.data_ptr(), d_out, d_in, packed.data_ptr(), s_w.data_ptr(),
+                                              ws.buf.data_ptr(), ws.bytes, _stream(stream)),
+           "hgf_quantize_pack_weights_b3")
+    return packed, s_w
+
+
+def hgf_unpack_weights_b3(packed: torch.Tensor, d_out: int, d_in: int, stream=None) -> torch.Tensor:
+    T = torch.empty((d_out, d_in), dtype=torch.int8, device=packed.device)
+    _check(lib().hgf_unpack_weights_b3(packed.data_ptr(), d_out, d_in, T.data_ptr(), _stream(stream)),
+           "hgf_unpack_weights_b3")
+    return T
+
+
+def hgf_linear_forward_b3(x: torch.Tensor, layer: "Layer", ws: Workspace, y: Optional[torch.Tensor] = None,
+                          acc_debug: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """One HGF linear whose `layer.packed` is a base-3 buffer (M <= 4)."""
+    _dev(x, torch.float16, "x")
+    M, d_in = x.shape
+    if d_in != layer.d_in:
+        raise ValueError("x has the wrong d_in")
+    if y is None:
+        y = torch.empty((M, layer.d_out), dtype=torch.float16, device=x.device)
+    _check(lib().hgf_linear_forward_b3(x.data_ptr(), M, ctypes.byref(layer.c), y.data_ptr(), _ptr(acc_debug),
+                                       ws.buf.data_ptr(), ws.bytes, _stream(stream)), "hgf_linear_forward_b3")
+    return y
 
 
 def hgf_static_scratch_bytes() -> int:

@@ -417,6 +417,69 @@ hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, c
     return run_large_group(x_f16, M, pairL, 2, ys, acc_debug_gate, ws, st, &po);
 }
 
+size_t hgf_packed_weight_bytes_b3(int d_out, int d_in)
+{
+    if (!dims_ok(d_in, d_out)) return 0;
+    return b3_packed_bytes(d_out, d_in);
+}
+
+hgf_status hgf_quantize_pack_weights_b3(const float *W, int d_out, int d_in, void *packed_out, float *s_w_out,
+                                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!W || !packed_out || !s_w_out) return HGF_ERR_NULL;
+    if (!dims_ok(d_in, d_out)) return HGF_ERR_SHAPE;
+    if (!aligned16(packed_out)) return HGF_ERR_ALIGN;
+    if (!workspace) return HGF_ERR_WORKSPACE;
+    const Workspace ws = carve_workspace(workspace, 1, 1, 1, 0);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (launch_wsum(W, (size_t)d_out * d_in, ws.wsum, s_w_out, st) != hipSuccess) return HGF_ERR_DEVICE;
+    return from_hip(launch_pack_b3(W, d_out, d_in, s_w_out, reinterpret_cast<unsigned char *>(packed_out), st));
+}
+
+hgf_status hgf_unpack_weights_b3(const void *packed, int d_out, int d_in, int8_t *T_out, void *stream)
+{
+    if (!packed || !T_out) return HGF_ERR_NULL;
+    if (!dims_ok(d_in, d_out)) return HGF_ERR_SHAPE;
+    if (!aligned16(packed)) return HGF_ERR_ALIGN;
+    return from_hip(launch_unpack_b3(reinterpret_cast<const unsigned char *>(packed), d_out, d_in, T_out,
+                                     reinterpret_cast<hipStream_t>(stream)));
+}
+
+hgf_status hgf_linear_forward_b3(const void *x_f16, int M, const hgf_layer *L, void *y_f16, int32_t *acc_debug,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x_f16 || !y_f16) return HGF_ERR_NULL;
+    const hgf_status s = check_layer(L, M);
+    if (s != HGF_OK) return s;
+    if (!aligned16(x_f16) || !aligned16(y_f16)) return HGF_ERR_ALIGN;
+    if (!workspace) return HGF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return HGF_ERR_ALIGN;
+    const Workspace ws = carve_workspace(workspace, M, L->d_in, L->d_out, L->rank);
+    if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
+    if (L->ln_gamma || !b3_fits(M, L->d_in, L->rank)) return HGF_ERR_UNSUPPORTED;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // steps 1, 2, 5, 6 of Algorithm 1: the decode prologue (quantiser, partial sums of A x, their sum and SiLU)
+    ProParams pp;
+    pp.x = reinterpret_cast<const _Float16 *>(x_f16);
+    pp.xq = ws.xq;
+    pp.s_x = ws.s_x;
+    pp.rowsum = ws.rowsum;
+    pp.amax_zero = nullptr;
+    pp.quantize = 1;
+    pp.M = M;
+    pp.K = L->d_in;
+    pp.Kp = round_up(L->d_in, kTileCols);
+    pp.G = 1;
+    pp.L[0].A = reinterpret_cast<const _Float16 *>(L->A_f16);
+    pp.L[0].hpart = ws.hslices;
+    pp.L[0].rank = L->rank;
+    pp.L[0].rp = h_stride(L->rank > 0 ? L->rank : 1);
+    _Float16 *h16[kMaxGroup] = {ws.h16, nullptr, nullptr, nullptr};
+    if (launch_prologue(pp, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
+    return from_hip(launch_b3_decode(L->W_packed, ws, ws.h16, M, *L, y_f16, acc_debug, st));
+}
+
 size_t hgf_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 size_t hgf_static_scratch_needed(int M, int d_in, int d_out, int rank)

@@ -293,4 +293,12 @@ struct PairOut {                 // extra outputs of a SwiGLU pair launch (both 
 hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
                           void *const *ys, int32_t *acc_debug, hipStream_t st, const PairOut *pair_out = nullptr);
 
+// base-3 packing (five ternary weights per byte) and its few-token decode kernel
+size_t b3_packed_bytes(int d_out, int d_in);
+hipError_t launch_pack_b3(const float *W, int N, int K, const float *s_w, unsigned char *packed, hipStream_t st);
+hipError_t launch_unpack_b3(const unsigned char *packed, int N, int K, int8_t *T, hipStream_t st);
+bool b3_fits(int M, int K, int rank);
+hipError_t launch_b3_decode(const void *packed, const Workspace &ws, const _Float16 *h16, int M, const hgf_layer &L,
+                            void *y, int32_t *acc_debug, hipStream_t st);
+
 }  // namespace hgf
