@@ -443,6 +443,22 @@ def main() -> int:
             return res
         cases.update(b3_cases())
         torch.cuda.empty_cache()
+
+        # ---- differential-attention decode step: the K and V caches are streamed once
+        def attn_case(B, L, H, d_h):
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(4700)
+            q = torch.randn((B, 2 * H, d_h), generator=gen, device="cuda").half()
+            k = torch.randn((B, L, 2 * H, d_h), generator=gen, device="cuda").half()
+            v = torch.randn((B, L, H, d_h), generator=gen, device="cuda").half()
+            lens = torch.full((B,), L, dtype=torch.int32, device="cuda")
+            o = torch.empty((B, H, d_h), dtype=torch.float16, device="cuda")
+            wsp = torch.empty(hb.lib().hgf_diff_attention_workspace_bytes(B, L, H, d_h), dtype=torch.uint8, device="cuda")
+            t = time_steps(lambda: hb.hgf_diff_attention_decode(q, k, v, lens, 0.8, out=o, workspace=wsp), 20, 3)
+            return hbm(B * L * 3 * H * d_h * 2 + B * 3 * H * d_h * 2 + B * H * d_h * 2, t)
+        cases["diff_attention_decode_d4096_h32_B8_L4096"] = attn_case(8, 4096, 32, 64)
+        cases["diff_attention_decode_d512_h8_B64_L512"] = attn_case(64, 512, 8, 32)
+        torch.cuda.empty_cache()
         # ---- config 0: the single 256x256 linear at 8 tokens (cache-resident, launch bound)
         w0 = Workload(0, 8, 1, seed=0, ws=ws)
         s0 = time_steps(make_runner(w0, ws, use_graph), max(20, args.steps), args.warmup)

@@ -184,6 +184,29 @@ hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, c
                               int32_t *acc_debug_up, void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* ---------------------------------------------------------------- differential attention, one decode step
+ *
+ * The block that consumes the q, k, v projections (Sec. 2.4, Def. "Differential Attention"):
+ *     O = (softmax(Q1 K1^T / sqrt(d_h)) - lambda * softmax(Q2 K2^T / sqrt(d_h))) V,
+ * with the details the appendix implementation fixes: q and k hold 2 n_heads heads of d_h columns
+ * (heads 0 .. n_heads-1 are branch 1, the rest branch 2), v holds n_heads heads of d_h columns
+ * (V: d -> d/2), head h of both branches reads head h of v, and the difference is multiplied by 0.5.
+ * One decode step: for each sequence b the newest token's q attends to the cached positions
+ * 0 .. lens[b]-1 (its own k and v already appended by the caller).
+ *
+ *   q_f16        fp16 [B, 2 n_heads, d_h]
+ *   k_cache_f16  fp16 [B, L_max, 2 n_heads, d_h]      v_cache_f16  fp16 [B, L_max, n_heads, d_h]
+ *   lens         int32 [B] (device), 1 <= lens[b] <= L_max (0: that sequence's output is zero)
+ *   lambda       the scalar of the definition (its initial value there: 0.8 - 0.6 exp(-0.3 d))
+ *   out_f16      fp16 [B, n_heads, d_h], written
+ *   workspace    hgf_diff_attention_workspace_bytes(B, L_max, n_heads, d_h) bytes, 16-byte aligned
+ * d_h a power of two in 8 .. 128.  fp32 arithmetic; the caches are read once. */
+size_t hgf_diff_attention_workspace_bytes(int B, int L_max, int n_heads, int d_h);
+hgf_status hgf_diff_attention_decode(const void *q_f16, const void *k_cache_f16, const void *v_cache_f16,
+                                     const int32_t *lens, int B, int L_max, int n_heads, int d_h,
+                                     float lambda, void *out_f16, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
 /* ---------------------------------------------------------------- base-3 packing (1.6 bits per weight)
  *
  * The paper counts its backbone at log2 3 = 1.58 bits per weight (Sec. 4.1, Def. "Effective

@@ -185,6 +185,39 @@ def swiglu_pair_forward(x: np.ndarray, gate: Dict, up: Dict, dense_gemm: bool = 
             "gate": g, "up": u}
 
 
+def diff_attention_lambda_init(d: int) -> float:
+    """Sec. 2.4, Def. "Differential Attention": lambda_0 = 0.8 - 0.6 exp(-0.3 d)."""
+    return 0.8 - 0.6 * math.exp(-0.3 * d)
+
+
+def diff_attention_decode(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, lens: Sequence[int],
+                          lam: float) -> np.ndarray:
+    """One decode step of differential attention in fp64, written out head by head.
+    Sec. 2.4, Def. "Differential Attention":
+        O = (softmax(Q1 K1^T / sqrt(d_h)) - lambda softmax(Q2 K2^T / sqrt(d_h))) V,
+    with what the appendix implementation fixes: q, k hold 2H heads (0..H-1 branch 1, H..2H-1
+    branch 2) of d_h columns, v holds H heads of d_h columns, head h of both branches reads head
+    h of v, and the difference is multiplied by 0.5.  The newest token of sequence b attends
+    to the cached positions 0 .. lens[b]-1.
+    q [B, 2H, d_h], k_cache [B, L, 2H, d_h], v_cache [B, L, H, d_h] -> [B, H, d_h] fp64."""
+    B, L, H2, d_h = k_cache.shape
+    H = H2 // 2
+    out = np.zeros((B, H, d_h), dtype=np.float64)
+    for b in range(B):
+        n = int(lens[b])
+        if n == 0:
+            continue
+        for h in range(H):
+            a = []
+            for head in (h, H + h):
+                s = k_cache[b, :n, head, :].astype(np.float64) @ q[b, head, :].astype(np.float64) / math.sqrt(d_h)
+                e = np.exp(s - s.max())
+                pr = e / e.sum()
+                a.append(pr @ v_cache[b, :n, h, :].astype(np.float64))
+            out[b, h] = (a[0] - lam * a[1]) * 0.5
+    return out
+
+
 def stack_forward(layers: Sequence[Dict], wiring: Sequence[Tuple[int, int]],
                   x0: np.ndarray) -> List[np.ndarray]:
     """A chain of HGF linears: layer i reads slot wiring[i][0] and writes slot

@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
     L.hgf_static_scratch_needed.argtypes = [ci, ci, ci, ci]
     L.hgf_linear_forward_static.restype = ci
     L.hgf_linear_forward_static.argtypes = [vp, ci, ctypes.POINTER(hgf_layer), vp, vp, vp]
+    L.hgf_diff_attention_workspace_bytes.restype = sz
+    L.hgf_diff_attention_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    L.hgf_diff_attention_decode.restype = ci
+    L.hgf_diff_attention_decode.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, vp, vp, sz, vp]
     L.hgf_packed_weight_bytes_b3.restype = sz
     L.hgf_packed_weight_bytes_b3.argtypes = [ci, ci]
     L.hgf_quantize_pack_weights_b3.restype = ci
@@ -294,6 +298,31 @@ def hgf_swiglu_forward(x: torch.Tensor, gate: Layer, up: Layer, ws: Workspace, z
                                     _ptr(amax), _ptr(acc_debug_gate), _ptr(acc_debug_up), ws.buf.data_ptr(),
                                     ws.bytes, _stream(stream)), "hgf_swiglu_forward")
     return z
+
+
+def hgf_diff_attention_decode(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, lens: torch.Tensor,
+                              lam: float, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """One decode step of differential attention: q fp16 [B, 2H, d_h], k_cache [B, L, 2H, d_h],
+    v_cache [B, L, H, d_h], lens int32 [B] -> fp16 [B, H, d_h]."""
+    for t, n in ((q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _dev(t, torch.float16, n)
+    _dev(lens, torch.int32, "lens")
+    B, L, H2, d_h = k_cache.shape
+    H = H2 // 2
+    if tuple(q.shape) != (B, H2, d_h) or tuple(v_cache.shape) != (B, L, H, d_h) or tuple(lens.shape) != (B,):
+        raise ValueError("shapes: q [B, 2H, d_h], k_cache [B, L, 2H, d_h], v_cache [B, L, H, d_h], lens [B]")
+    need = lib().hgf_diff_attention_workspace_bytes(B, L, H, d_h)
+    if need == 0:
+        raise ValueError("unsupported attention dimensions")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty((B, H, d_h), dtype=torch.float16, device=q.device)
+    _check(lib().hgf_diff_attention_decode(q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), lens.data_ptr(), B, L,
+                                           H, d_h, float(lam), out.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel(), _stream(stream)), "hgf_diff_attention_decode")
+    return out
 
 
 def hgf_packed_weight_bytes_b3(d_out: int, d_in: int) -> int:

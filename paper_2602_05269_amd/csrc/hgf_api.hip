@@ -417,6 +417,35 @@ hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, c
     return run_large_group(x_f16, M, pairL, 2, ys, acc_debug_gate, ws, st, &po);
 }
 
+namespace {
+bool attn_dims_ok(int B, int L_max, int n_heads, int d_h)
+{
+    if (B < 1 || L_max < 1 || n_heads < 1 || d_h < 8 || d_h > 128 || (d_h & (d_h - 1)) != 0) return false;
+    // the caches are addressed with 32-bit byte offsets per sequence
+    return (long long)L_max * 2 * n_heads * d_h * 2 < (1LL << 31) && (long long)B * n_heads < (1LL << 16);
+}
+}  // namespace
+
+size_t hgf_diff_attention_workspace_bytes(int B, int L_max, int n_heads, int d_h)
+{
+    return attn_dims_ok(B, L_max, n_heads, d_h) ? diff_attn_workspace_bytes(B, L_max, n_heads, d_h) : 0;
+}
+
+hgf_status hgf_diff_attention_decode(const void *q_f16, const void *k_cache_f16, const void *v_cache_f16,
+                                     const int32_t *lens, int B, int L_max, int n_heads, int d_h, float lambda,
+                                     void *out_f16, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q_f16 || !k_cache_f16 || !v_cache_f16 || !lens || !out_f16) return HGF_ERR_NULL;
+    if (!attn_dims_ok(B, L_max, n_heads, d_h)) return HGF_ERR_SHAPE;
+    if (!aligned16(q_f16) || !aligned16(k_cache_f16) || !aligned16(v_cache_f16) ||
+        (reinterpret_cast<uintptr_t>(out_f16) & 1u) || (reinterpret_cast<uintptr_t>(lens) & 3u))
+        return HGF_ERR_ALIGN;
+    if (!workspace || workspace_bytes < diff_attn_workspace_bytes(B, L_max, n_heads, d_h)) return HGF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return HGF_ERR_ALIGN;
+    return from_hip(launch_diff_attn(q_f16, k_cache_f16, v_cache_f16, lens, B, L_max, n_heads, d_h, lambda, out_f16,
+                                     workspace, reinterpret_cast<hipStream_t>(stream)));
+}
+
 size_t hgf_packed_weight_bytes_b3(int d_out, int d_in)
 {
     if (!dims_ok(d_in, d_out)) return 0;

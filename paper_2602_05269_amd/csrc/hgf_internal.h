@@ -293,6 +293,11 @@ struct PairOut {                 // extra outputs of a SwiGLU pair launch (both 
 hipError_t launch_prefill(const Workspace &ws, _Float16 *const *h16, int M, const hgf_layer *layers, int G,
                           void *const *ys, int32_t *acc_debug, hipStream_t st, const PairOut *pair_out = nullptr);
 
+// differential attention, one decode step
+size_t diff_attn_workspace_bytes(int B, int L_max, int n_heads, int d_h);
+hipError_t launch_diff_attn(const void *q, const void *k, const void *v, const int32_t *lens, int B, int L_max,
+                            int n_heads, int d_h, float lambda, void *out, void *workspace, hipStream_t st);
+
 // base-3 packing (five ternary weights per byte) and its few-token decode kernel
 size_t b3_packed_bytes(int d_out, int d_in);
 hipError_t launch_pack_b3(const float *W, int N, int K, const float *s_w, unsigned char *packed, hipStream_t st);

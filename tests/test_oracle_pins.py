@@ -382,6 +382,42 @@ def test_layer_with_layernorm_quantises_the_normalised_input_only():
                        rtol=1e-13, atol=1e-15)
 
 
+def test_diff_attention_against_library_attention_and_special_cases():
+    """The differential-attention decode step against torch's scaled_dot_product_attention (a
+    library routine; the last row of a causal attention is the decode step), and the cases the
+    definition fixes: identical branches give (1 - lambda)/2 times ordinary attention, a single
+    cached position returns (1 - lambda)/2 times its value row, equal keys average the values."""
+    import torch
+    rng = np.random.default_rng(17)
+    B, L, H, d = 2, 37, 3, 16
+    q = rng.standard_normal((B, 2 * H, d)).astype(np.float16)
+    k = rng.standard_normal((B, L, 2 * H, d)).astype(np.float16)
+    v = rng.standard_normal((B, L, H, d)).astype(np.float16)
+    lens = [L, 11]
+    lam = 0.37
+    out = orc.diff_attention_decode(q, k, v, lens, lam)
+    for b in range(B):
+        n = lens[b]
+        tq = torch.from_numpy(q[b].astype(np.float64))[:, None, :]                     # [2H, 1, d]
+        tk = torch.from_numpy(k[b, :n].astype(np.float64)).permute(1, 0, 2)            # [2H, n, d]
+        tv = torch.from_numpy(v[b, :n].astype(np.float64)).permute(1, 0, 2)            # [H, n, d]
+        a1 = torch.nn.functional.scaled_dot_product_attention(tq[:H], tk[:H], tv)[:, 0].numpy()
+        a2 = torch.nn.functional.scaled_dot_product_attention(tq[H:], tk[H:], tv)[:, 0].numpy()
+        assert np.allclose(out[b], (a1 - lam * a2) * 0.5, rtol=1e-12, atol=1e-14)
+    q2, k2 = q.copy(), k.copy()
+    q2[:, H:], k2[:, :, H:] = q2[:, :H], k2[:, :, :H]                                   # both branches alike
+    same = orc.diff_attention_decode(q2, k2, v, [L, L], lam)
+    one = orc.diff_attention_decode(q2, k2, v, [L, L], 0.0)                             # lambda 0: half of branch 1
+    assert np.allclose(same, (1 - lam) * one, rtol=1e-12, atol=1e-14)
+    single = orc.diff_attention_decode(q, k, v, [1, 1], lam)
+    assert np.allclose(single, (1 - lam) * 0.5 * v[:, 0].astype(np.float64), rtol=1e-12)
+    k3 = np.broadcast_to(k[:, :1], k.shape).copy()                                      # every key alike
+    avg = orc.diff_attention_decode(q, k3, v, [L, L], lam)
+    assert np.allclose(avg, (1 - lam) * 0.5 * v.astype(np.float64).mean(axis=1), rtol=1e-10, atol=1e-12)
+    assert orc.diff_attention_lambda_init(0) == pytest.approx(0.2) and orc.diff_attention_lambda_init(64) == pytest.approx(0.8, abs=1e-8)
+    assert orc.diff_attention_lambda_init(2) == pytest.approx(0.8 - 0.6 * math.exp(-0.6))
+
+
 def test_stack_is_the_chain_of_fp16_rounded_layers():
     a = _case(21, 3, 64, 48, 8)
     b = _case(22, 3, 48, 32, 8)
