@@ -174,6 +174,53 @@ def recorded_traffic():
     return None
 
 
+def timeline(wl: Workload, ws: hb.Workspace, ph0: int) -> int:
+    """Medians over the workgroups of the in-kernel time stamps of phases ph0 .. ph0+3 of the first
+    whole-stack launch of a step, in microseconds after the moment the last workgroup stored the
+    last output of the phase before (the earliest moment the phase's input is complete)."""
+    for _ in range(3):
+        hb.hgf_stack_forward(wl.stack, ws)
+    torch.cuda.synchronize()
+    plain = time_steps(lambda: hb.hgf_stack_forward(wl.stack, ws), 10, 2)
+    buf = torch.zeros((256, hb.TRACE_ROLES, hb.TRACE_PHASES, hb.TRACE_IDS), dtype=torch.int64, device="cuda")
+    hb.hgf_set_stack_trace(buf, ph0)
+    try:
+        traced = time_steps(lambda: hb.hgf_stack_forward(wl.stack, ws), 10, 2)
+        buf.zero_()
+        torch.cuda.synchronize()
+        hb.hgf_stack_forward(wl.stack, ws)
+        torch.cuda.synchronize()
+    finally:
+        hb.hgf_set_stack_trace(None)
+    t = buf.cpu().numpy().astype(np.float64) / 100.0          # 100 MHz clock -> microseconds
+    t[t == 0] = np.nan
+    # NOTE: a step is two launches; the second overwrites the first's stamps, both walk the same shapes
+    print(f"ms per step: {plain * 1e3:.4f} without stamps, {traced * 1e3:.4f} with")
+    names = {"contract": ["enter", "tokens complete", "absmax agreed", "quantised", "first unit contracted", "last unit contracted"],
+             "slice": ["enter", "own slices stored", "SiLU(A x) in LDS", "own slice multiplied"],
+             "unit": ["enter", "SiLU(A x) seen", "first unit complete", "last unit complete", "last unit stored",
+                      "first unit's B h done"]}
+    for k in range(1, hb.TRACE_PHASES):
+        ph = ph0 + k
+        prev_done = np.nanmax(t[:, 9, k - 1, 4])
+        this_done = np.nanmax(t[:, 9, k, 4])
+        busy = ~np.isnan(t[:, 9, k, 2])
+        print(f"phase {ph}: {int(busy.sum())} workgroups own units; {this_done - prev_done:.2f} us from the last store "
+              f"of phase {ph - 1} to the last store of phase {ph}")
+        rel = t[busy] - prev_done
+        med = lambda a: float(np.nanmedian(a))
+        c = rel[:, 0:8, k, :]
+        print("  contracting wavefronts (per workgroup: first / last of the eight; then the median over workgroups)")
+        for i, nm in enumerate(names["contract"]):
+            print(f"    {nm:24s} first {med(np.nanmin(c[:, :, i], axis=1)):6.2f}   last {med(np.nanmax(c[:, :, i], axis=1)):6.2f}")
+        for i, nm in enumerate(names["slice"]):
+            print(f"  slice wavefront  {nm:22s} {med(rel[:, 8, k, i]):6.2f}")
+        for i, nm in enumerate(names["unit"]):
+            print(f"  unit wavefront   {nm:22s} {med(rel[:, 9, k, i]):6.2f}   (latest workgroup {float(np.nanmax(rel[:, 9, k, i])):6.2f})")
+        print(f"  loader 0         first tile requested  {med(rel[:, 10, k, 0]):6.2f}")
+    return 0
+
+
 def mfma_probe() -> int:
     """The yardstick beside the published int8 peak: what the matrix cores sustain on this
     layer's kind of operands once the chip has settled its clock under their power."""
@@ -246,6 +293,9 @@ def main() -> int:
     ap.add_argument("--mfma-probe", action="store_true",
                     help="print the int8 rate a loop of nothing but the prefill kernel's MFMA sustains, "
                          "for constant, ternary-code x random and random operands, and exit")
+    ap.add_argument("--timeline", type=int, default=-1, metavar="PHASE",
+                    help="print the time line of four phases of the whole-stack launch from this phase on "
+                         "(time stamps taken inside the kernel) and exit")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="run only a plain copy kernel of this many MiB (counter calibration)")
     args = ap.parse_args()
@@ -270,6 +320,8 @@ def main() -> int:
 
     # ---- primary: 7B-shape FFN decode, M = 1, distinct weights every block (HBM-cold)
     wl = Workload(4, args.tokens, args.blocks, seed=4000, ws=ws)
+    if args.timeline >= 0:
+        return timeline(wl, ws, args.timeline)
     run = make_runner(wl, ws, use_graph)
     sec, ev_sec = time_steps(run, args.steps, args.warmup, events=True)
     gbs = wl.bytes / sec / 1e9

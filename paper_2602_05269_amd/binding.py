@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
     L.hgf_set_single_launch.argtypes = [ci]
     L.hgf_set_wait_limit.restype = None
     L.hgf_set_wait_limit.argtypes = [ci]
+    L.hgf_set_stack_trace.restype = None
+    L.hgf_set_stack_trace.argtypes = [vp, sz, ci]
     L.hgf_profile_enable.restype = None
     L.hgf_profile_enable.argtypes = [ci]
     L.hgf_profile_collect.restype = ci
@@ -165,6 +167,17 @@ def hgf_set_wait_limit(tries: int) -> None:
     """Test hook: every wait between workgroups of the whole-stack launch gives up after `tries`
     tries (0: the default bound of about a second)."""
     lib().hgf_set_wait_limit(int(tries))
+
+
+TRACE_ROLES, TRACE_PHASES, TRACE_IDS = 11, 4, 6
+
+
+def hgf_set_stack_trace(buf: Optional[torch.Tensor], first_phase: int = 0) -> None:
+    """Time stamps of the whole-stack launch into `buf` (int64 [256, 11, 4, 6] on the device); None: off."""
+    if buf is None:
+        lib().hgf_set_stack_trace(None, 0, 0)
+    else:
+        lib().hgf_set_stack_trace(buf.data_ptr(), buf.numel() * buf.element_size(), int(first_phase))
 
 
 def hgf_profile_enable(on: bool) -> None:

@@ -711,4 +711,9 @@ void hgf_set_single_launch(int level) { g_launch_level = level < 0 ? 0 : (level 
 
 void hgf_set_wait_limit(int tries) { set_stack_wait_limit(tries); }
 
+void hgf_set_stack_trace(void *device_buffer, size_t bytes, int first_phase)
+{
+    set_stack_trace(reinterpret_cast<unsigned long long *>(device_buffer), bytes, first_phase);
+}
+
 }  // extern "C"

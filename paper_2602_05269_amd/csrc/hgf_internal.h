@@ -252,12 +252,19 @@ struct StackPhase {                                    // 24 bytes
     unsigned src_off;             // else: byte offset of their exchange copy
     unsigned mail_off;            // byte offset of the phase's partial sums of A x
 };
+// Time stamps of the whole-stack launch (a measurement aid, off unless a buffer is set): each
+// role's first lane notes the device-wide 100 MHz clock at fixed points of kTracePhases
+// consecutive phases; the words leave through LDS at the end of the launch.
+constexpr int kTraceRoles = 11;       // contracting wavefronts 0..7, slice wavefront, unit wavefront, loader 0
+constexpr int kTracePhases = 4;
+constexpr int kTraceIds = 6;
 struct StackParams {
-    int M, nphases, nwg, reserved;
+    int M, nphases, nwg, trace_ph0;   // trace_ph0: first traced phase
+    unsigned long long *trace;        // null, or [nwg][kTraceRoles][kTracePhases][kTraceIds] time stamps
     int32_t *flags;               // [2] sticky error, [4] launch counter, [5] workgroups done, [6], [7] extents used
     unsigned char *xchg;          // two sets of kStackSetBytes
     unsigned act_used, mail_used;
-    int xstride, h_par, tile_off, h_off, unit_off, unit_stride, unit_alpha, jx_off, ring_off, ring_slots;   // LDS layout
+    int xstride, h_par, tile_off, tile_par, h_off, unit_off, unit_stride, unit_alpha, jx_off, ring_off, ring_slots;   // LDS layout
     int mem_polls, lds_polls;     // tries after which a wait for another workgroup / another wavefront gives up
     StackPhase ph[kStackMaxPhases];
     StackLayer L[kStackMaxLayers];
@@ -285,6 +292,7 @@ bool plan_fused(FusedParams &p, size_t *lds_bytes);
 hipError_t launch_fused(const FusedParams &p, size_t lds_bytes, hipStream_t st);
 bool plan_stack(StackParams &p, size_t *lds_bytes);
 void set_stack_wait_limit(int tries);
+void set_stack_trace(unsigned long long *buf, size_t bytes, int first_phase);
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st);
 struct PairOut {                 // extra outputs of a SwiGLU pair launch (both nullable)
     int32_t *acc_debug2;         // the up projection's int32 accumulators

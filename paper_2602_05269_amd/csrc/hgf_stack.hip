@@ -42,7 +42,7 @@ constexpr int kLoaders = 2;            // loader wavefronts (8, 9): each feeds f
 constexpr int kFeed = kStream / kLoaders;
 constexpr int kWaves = kStream + kLoaders + 2;
 constexpr int kWindow = 3;             // groups of kFeed weight tiles a loader keeps in flight
-constexpr int kMinRing = kWindow + 4;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow)
+constexpr int kMinRing = kWindow + 5;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow; even)
 constexpr int kMaxRing = 48;
 constexpr int kMaxUnits = 16;          // units per workgroup and phase at most
 constexpr int kLdsPollsDefault = 1 << 22;   // bound of a wait on LDS (about a second)
@@ -66,7 +66,22 @@ struct Control {                       // LDS words shared by the two sides; [2]
     int failed;                        // a wait of a loader, contracting or slice wavefront has expired
     int ready[kStream];                // weight tiles of the wavefront's ring that have landed in LDS, in all
     int consumed[kStream];             // ... and how many of them it has read
+    unsigned long long stamps[kTraceRoles][kTracePhases][kTraceIds];   // time stamps (only with p.trace set)
 };
+
+// Notes the device-wide clock for (role, phase, id) when tracing is on and the phase is traced.
+#define HGF_STAMP(role, ph, id)                                                                        \
+    do {                                                                                               \
+        if (p.trace != nullptr && (threadIdx.x & 63) == 0 && (unsigned)((ph)-p.trace_ph0) < (unsigned)kTracePhases) \
+            ctl->stamps[role][(ph)-p.trace_ph0][id] = wall_clock64();                                  \
+    } while (0)
+__device__ __forceinline__ void trace_flush(const StackParams &p, Control *ctl, int c, int role)
+{
+    if (p.trace == nullptr) return;
+    const unsigned long long *src = &ctl->stamps[role][0][0];
+    unsigned long long *dst = p.trace + ((size_t)c * kTraceRoles + role) * kTracePhases * kTraceIds;
+    for (int e = threadIdx.x & 63; e < kTracePhases * kTraceIds; e += 64) dst[e] = src[e];
+}
 
 __device__ __forceinline__ int lds_load(const int *p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
 __device__ __forceinline__ v4u load16_agent(rsrc_t r, unsigned off, bool ok = true)
@@ -86,7 +101,7 @@ __device__ __forceinline__ float silu_fast(float h) { return h * __builtin_amdgc
 __device__ __forceinline__ float tanh_fast(float a) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_fast(2.0f * a)); }
 // What both sides derive from a phase's entry in the kernel arguments (all wave-uniform).
 struct PhaseShape {
-    int K, Kp, KT, TPW, G, first;      // first: index of the phase's first layer
+    int K, Kp, KT, TPW, TPP, G, first; // TPW: k-tiles per contracting wavefront; TPP: pairs of them; first: the phase's first layer
     int units, nunits;                 // row-blocks of the phase; of this workgroup
     int us1, us2, us3;                 // running sums of the layers' row-blocks (0x7fffffff beyond G)
 };
@@ -98,6 +113,7 @@ __device__ __forceinline__ PhaseShape shape_of(const StackParams &p, int ph, int
     s.Kp = (s.K + kTileCols - 1) / kTileCols * kTileCols;
     s.KT = s.Kp / kTileCols;
     s.TPW = (s.KT + kStream - 1) / kStream;
+    s.TPP = (s.TPW + 1) / 2;
     s.G = P.G;
     s.first = P.first_layer;
     const int r0 = (p.L[s.first].N + kTileRows - 1) / kTileRows;
@@ -152,6 +168,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
         }
         __builtin_amdgcn_s_sleep(1);
     }
+    HGF_STAMP(w, ph, 1);
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         float amax = 0.0f;
@@ -171,6 +188,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     while (!failed && lds_load(&ctl->sync) < sync_target) {
         if (++polls >= p.lds_polls) failed = true;
     }
+    HGF_STAMP(w, ph, 2);
     polls = 0;
 #pragma clang loop unroll(disable)
     while (!unit_done && !failed) {
@@ -199,8 +217,15 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
                 sum += q;
                 q2[e >> 2] |= (uint32_t)(q & 0xff) << (8 * (e & 3));
             }
-            if (m < p.M && j < S.TPW && kt < S.KT)
-                *reinterpret_cast<uint2 *>(lds + m * p.xstride + kt * kTileCols + pc * 8) = make_uint2(q2[0], q2[1]);
+            // The tile's 128 codes are stored in the order the contraction reads them: column
+            // 32 t + 16 h + 4 s + b of the tile at byte (4 h + s) 16 + 4 t + b, so that the sixteen
+            // columns one MFMA operand register set needs for shift s (all t, all b) are contiguous.
+            // The lane's eight columns are t = pc / 4, h = (pc / 2) % 2, s = 2 (pc % 2) and s + 1.
+            if (m < p.M && j < S.TPW && kt < S.KT) {
+                unsigned char *at = lds + m * p.xstride + kt * kTileCols + (((pc >> 1) & 1) * 4 + (pc & 1) * 2) * 16 + (pc >> 2) * 4;
+                *reinterpret_cast<uint32_t *>(at) = q2[0];
+                *reinterpret_cast<uint32_t *>(at + 16) = q2[1];
+            }
         }
         sum = wave_sum(sum);
         if (l == 0 && m < p.M) {
@@ -250,6 +275,7 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
         const StackLayer *L = p.L + S.first;
+        if (ld == 0) HGF_STAMP(kStream + 2, ph, 0);
         for (int i = 0; i < S.nunits; ++i) {
             const int u = c + i * p.nwg;
             int g = 0, first = 0;
@@ -259,7 +285,7 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
             const unsigned rows = (unsigned)((L[g].N + kTileRows - 1) / kTileRows);
             const rsrc_t wr = make_rsrc(L[g].packed, rows * S.KT * kTileBytes);
             const unsigned row = (unsigned)(u - first) * S.KT;
-            for (int j = 0; j < S.TPW; ++j) {
+            for (int j = 0; j < 2 * S.TPP; ++j) {   // (an odd count is padded with a void tile: the contraction goes in pairs)
                 // room in the rings?  While there is none nothing is gained by keeping the
                 // window open: let everything land, publish it, and wait for the readers.
                 if (n - freed >= p.ring_slots) {
@@ -294,6 +320,7 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     publish(n);
+    if (ld == 0) trace_flush(p, ctl, c, kStream + 2);
     if (failed && l == 0) {
         lds_poke(failed_at, 1);
         __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -325,6 +352,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             sync_target += kStream;
             if (lds_load(&ctl->failed) != 0) failed = true;
             const bool was = failed;
+            HGF_STAMP(w, ph, 0);
             if (p.M == 1) fetch_quantise<1>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
             else if (p.M == 2) fetch_quantise<2>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
             else fetch_quantise<4>(p, S, xr, ext, lds, ctl, w, ph, sync_target, failed);
@@ -332,59 +360,68 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
                 __hip_atomic_store(&ctl->failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            HGF_STAMP(w, ph, 3);
         }
 
-        // ---- contraction with the 16x16x64 MFMA: the tokens (at most four) are rows of A, a
-        //      tile's 32 weight rows are the columns of B in two halves (nb), its 128 columns two
-        //      k-blocks (kb): four MFMAs of 4 passes per tile, where the 32x32x32 form, whose
-        //      operand layout the packed tile has, takes four of 8 passes.  The tile sits in LDS,
-        //      so each lane simply reads the dwords that form needs: lane (n = l%16, kq = l/16)
-        //      wants weight row nb*16+n, columns kb*64 + kq*16 + 0..15, which the packed layout
-        //      keeps in dword kb*2 + kq/2 of the 16 bytes of lane (nb*16 + n) + 32*(kq%2).
+        // ---- contraction with the 16x16x64 MFMA, two k-tiles to a step.  The tokens (at most
+        //      four) are rows of A, sixteen weight rows the columns of B.  A packed tile keeps, for
+        //      weight row r and k-half h, sixteen bytes (lane r + 32 h of the 32x32x32 layout) whose
+        //      dword t holds the codes of columns 32 t + 16 h + 4 s + b at bits 8 b + 2 s.  Lane
+        //      (n = l%16, kq = l/16) reads exactly those sixteen bytes, of tile kq/2 of the pair and
+        //      k-half kq%2, with one conflict-free 16-byte LDS read per row half nb; masking them
+        //      with 0x03030303 << 2 s leaves, in place, the sixteen codes of shift s times 4^s:
+        //      an operand of an MFMA whose k-index runs over (tile, h, t, b) -- no shifts.  (For
+        //      s = 3 the dword is shifted right once first, so that 2 << 6 does not overflow int8:
+        //      scale 32.)  Each shift has accumulators of its own; at the end of a unit they are
+        //      divided by their scales -- exactly: every term is a multiple -- and added.  The
+        //      tokens' image in LDS is stored in the matching order (fetch_quantise), so the A
+        //      operand of shift s is one 16-byte read as well.  20 vector instructions unpack a
+        //      tile where shift-and-mask of single dwords took 28, and the reads of the tile are
+        //      two instead of four conflicting ones: the step is bound by instruction issue.
         //      A wavefront issues its MFMAs and its other vector instructions one after the other
         //      (the other contracting wavefront of the SIMD fills the gaps), so everything that is
         //      not contraction is kept out of the step: scalar conditions, no branches but the
-        //      rare waits, ring bookkeeping every fourth step.  The operands of the next step are
+        //      rare waits, ring bookkeeping every other step.  The operands of the next step are
         //      read from LDS while this step computes.
-        int *tiles = reinterpret_cast<int *>(lds + p.tile_off) + par * kMaxUnits * kMaxFusedM * kTileRows;
+        int *tiles = reinterpret_cast<int *>(lds + p.tile_off) + par * p.tile_par;
         const int n16 = l & 15, kq = l >> 4;
-        const unsigned char *tlane = lds + p.ring_off + (size_t)w * p.ring_slots * kTileBytes +
-                                     (n16 + 32 * (kq & 1)) * 16 + (kq >> 1) * 4;
-        const int xbase = (n16 < p.M ? n16 : 0) * p.xstride + kq * 16;    // this lane's token row
-        const int zbase = p.jx_off + kMaxFusedM * 1024 + kq * 16;         // 128 bytes of zeros
-        const int total = S.nunits * S.TPW;
+        const unsigned char *tlane = lds + p.ring_off + (size_t)w * p.ring_slots * kTileBytes + (kq >> 1) * kTileBytes +
+                                     (n16 + 32 * (kq & 1)) * 16;
+        // this lane's token row, at its tile of the pair and its k-half; and 128 bytes of zeros
+        const int xbase = (n16 < p.M ? n16 : 0) * p.xstride + ((kq >> 1) * kStream + w) * kTileCols + (kq & 1) * 64;
+        const int zbase = p.jx_off + kMaxFusedM * 1024 + (kq & 1) * 64;
+        const int total = S.nunits * S.TPP;             // steps: pairs of tiles
         const unsigned long long token_rows = __builtin_amdgcn_ballot_w64(n16 < p.M);
         unsigned long long exec_save;
         struct Ops {
-            unsigned t[2][2];           // [nb][kb]: 16 two-bit codes each
-            v4i x[2];                   // [kb]: 16 quantised columns of the lane's token
+            v4u t[2];                   // [nb]: the lane's sixteen bytes of codes of row half nb
+            v4i x[4];                   // [s]: the lane's token's sixteen columns of shift s
         };
         Ops o0, o1;
-        // requests the operands of step `st` (k-turn j of its row-block): the tile's dwords from
-        // the ring (waiting, if the contraction has caught up with the loader, until the tile has
+        // requests the operands of step `st` (pair jp of its row-block): the tiles' bytes from the
+        // ring (waiting, if the contraction has caught up with the loader, until both tiles have
         // landed) and the tokens' columns -- zeros where the row-block has no k-tile for this
-        // wavefront in its last turn, so that the MFMAs need no condition.  Past the phase's last
-        // step the requests still go out, to addresses that are valid and hold nothing of
-        // interest: requests under a condition would make every wait on LDS a wait for all.
-        auto operands = [&](Ops &o, int j, int st) __attribute__((always_inline)) {
+        // wavefront (the second tile of its last pair, or a void turn), so that the MFMAs need no
+        // condition.  Past the phase's last step the requests still go out, to addresses that are
+        // valid and hold nothing of interest: requests under a condition would make every wait on
+        // LDS a wait for all.
+        auto operands = [&](Ops &o, int jp, int st) __attribute__((always_inline)) {
             const bool real = st < total;
-            if (__builtin_expect(real && known < gs + st + 1, 0)) {
+            if (__builtin_expect(real && known < gs + 2 * st + 2, 0)) {
                 int spins = 0;
 #pragma clang loop unroll(disable)
                 do {
                     known = lds_load(&ctl->ready[w]);
                     if (++spins >= p.lds_polls) failed = true;
-                } while (known < gs + st + 1 && !failed);
+                } while (known < gs + 2 * st + 2 && !failed);
             }
-            const unsigned char *ta = tlane + slot * kTileBytes;
-            o.t[0][0] = *reinterpret_cast<const unsigned *>(ta);
-            o.t[0][1] = *reinterpret_cast<const unsigned *>(ta + 8);
-            o.t[1][0] = *reinterpret_cast<const unsigned *>(ta + 256);
-            o.t[1][1] = *reinterpret_cast<const unsigned *>(ta + 264);
-            const int next = slot + 1 == p.ring_slots ? 0 : slot + 1;
+            const unsigned char *ta = tlane + slot * kTileBytes;        // (the ring holds an even number of tiles)
+            o.t[0] = *reinterpret_cast<const v4u *>(ta);
+            o.t[1] = *reinterpret_cast<const v4u *>(ta + 256);
+            const int next = slot + 2 == p.ring_slots ? 0 : slot + 2;
             slot = real ? next : slot;
-            const int kt = j * kStream + w;
-            const unsigned char *xa = lds + (kt < S.KT ? xbase + kt * kTileCols : zbase);
+            const int kt = (2 * jp + (kq >> 1)) * kStream + w;           // this lane's tile of the pair
+            const int xa = kt < S.KT ? xbase + 2 * jp * kStream * kTileCols : zbase;
             // Only the lanes of the tokens' rows read: a read by all 64 lanes costs LDS 16 times
             // the bandwidth, and LDS is what the eight contracting wavefronts share.  The lanes are
             // switched off around the reads by hand: a branch would make the compiler wait here for
@@ -392,46 +429,66 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             asm volatile("s_mov_b64 %[save], exec\n\t"
                          "s_mov_b64 exec, %[rows]\n\t"
                          "ds_read_b128 %[a], %[at]\n\t"
-                         "ds_read_b128 %[b], %[at] offset:64\n\t"
+                         "ds_read_b128 %[b], %[at] offset:16\n\t"
+                         "ds_read_b128 %[c], %[at] offset:32\n\t"
+                         "ds_read_b128 %[d], %[at] offset:48\n\t"
                          "s_mov_b64 exec, %[save]"
-                         : [a] "=&v"(o.x[0]), [b] "=&v"(o.x[1]), [save] "=&s"(exec_save)
-                         : [at] "v"(lds_offset(xa)), [rows] "s"(token_rows)
+                         : [a] "=&v"(o.x[0]), [b] "=&v"(o.x[1]), [c] "=&v"(o.x[2]), [d] "=&v"(o.x[3]), [save] "=&s"(exec_save)
+                         : [at] "v"(lds_offset(lds + xa)), [rows] "s"(token_rows)
                          : "memory");
         };
+        auto masked = [](const v4u t, unsigned m) __attribute__((always_inline)) {
+            return (v4i){(int)(t[0] & m), (int)(t[1] & m), (int)(t[2] & m), (int)(t[3] & m)};
+        };
         int ci = 0, cj = 0;
-        v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};      // weight rows 0..15 and 16..31 of the unit; element m: token m
+        // [nb][s]: weight rows 0..15 and 16..31 of the unit, shift s (scale 1, 4, 16, 32); element m: token m
+        v4i acc[2][4];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int sh = 0; sh < 4; ++sh) acc[nb][sh] = (v4i){0, 0, 0, 0};
         // one step: request the next step's operands into the other register set, then contract
         // this step's (two named sets, taken in turn: copying one set into the other would wait
         // for the requests just made and undo the overlap)
         auto step = [&](const Ops &oc, Ops &on, int st) __attribute__((always_inline)) {
-            const int nj = cj + 1 == S.TPW ? 0 : cj + 1;
+            const int nj = cj + 1 == S.TPP ? 0 : cj + 1;
             __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): this step's operands, requested a step ago
             __builtin_amdgcn_sched_barrier(0);
             operands(on, nj, st + 1);
             __builtin_amdgcn_sched_barrier(0);      // (the requests stay ahead of the MFMAs)
-            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[0], widen_codes(oc.t[0][0]), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[0], widen_codes(oc.t[1][0]), acc1, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[1], widen_codes(oc.t[0][1]), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[1], widen_codes(oc.t[1][1]), acc1, 0, 0, 0);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const v4u t = oc.t[nb];
+                const v4u t3 = {t[0] >> 1, t[1] >> 1, t[2] >> 1, t[3] >> 1};
+                acc[nb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[0], masked(t, 0x03030303u), acc[nb][0], 0, 0, 0);
+                acc[nb][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[1], masked(t, 0x0C0C0C0Cu), acc[nb][1], 0, 0, 0);
+                acc[nb][2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[2], masked(t, 0x30303030u), acc[nb][2], 0, 0, 0);
+                acc[nb][3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[3], masked(t3, 0x60606060u), acc[nb][3], 0, 0, 0);
+            }
             cj = nj;
-            if ((st & 3) == 3 || nj == 0) {         // tell the loader what it may overwrite
-                if (l == 0) __hip_atomic_store(&ctl->consumed[w], gs + st + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if ((st & 1) == 1 || nj == 0) {         // tell the loader what it may overwrite
+                if (l == 0) __hip_atomic_store(&ctl->consumed[w], gs + 2 * st + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             if (nj == 0) {
-                if (l < 16) {           // lanes 0..15 hold tokens 0..3 of weight rows l (acc0) and 16 + l (acc1)
+                if (l < 16) {           // lanes 0..15 hold tokens 0..3 of weight rows l (nb 0) and 16 + l (nb 1)
 #pragma unroll
-                    for (int m = 0; m < kMaxFusedM; ++m)
-                        if (m < p.M) {
-                            __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + l, acc0[m], __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
-                            __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + 16 + l, acc1[m], __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
-                        }
+                    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                        for (int m = 0; m < kMaxFusedM; ++m)
+                            if (m < p.M) {
+                                const int sum = acc[nb][0][m] + (acc[nb][1][m] >> 2) + (acc[nb][2][m] >> 4) + (acc[nb][3][m] >> 5);
+                                __hip_atomic_fetch_add(tiles + (ci * kMaxFusedM + m) * kTileRows + 16 * nb + l, sum, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                            }
                 }
                 if (l == 0)
                     __hip_atomic_fetch_add(&ctl->arrived[par][ci], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                acc0 = (v4i){0, 0, 0, 0};
-                acc1 = (v4i){0, 0, 0, 0};
+                if (ci == 0) HGF_STAMP(w, ph, 4);
+                if (ci == S.nunits - 1) HGF_STAMP(w, ph, 5);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int sh = 0; sh < 4; ++sh) acc[nb][sh] = (v4i){0, 0, 0, 0};
                 ++ci;
             }
         };
@@ -440,8 +497,9 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             step(o0, o1, st);
             if (st + 1 < total) step(o1, o0, st + 1);
         }
-        gs += total;
+        gs += 2 * total;
     }
+    trace_flush(p, ctl, c, w);
 }
 
 // ------------------------------------------------------------------ slice and unit wavefronts
@@ -640,6 +698,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
         const PhaseShape S = shape_of(p, ph, c);
         const StackPhase &P = p.ph[ph];
         _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off + (ph & 1) * p.h_par);
+        HGF_STAMP(kStream, ph, 0);
 
         // ---- my slices of A x (step 5): needs only the columns of the slice, so it starts as
         //      soon as the row-blocks of the previous layer that cover them have been stored
@@ -655,6 +714,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                 else if (p.M == 2) job_xfetch<2>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
                 else job_xfetch<4>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
                 acc = job_mfma(jr, jx, acc);
+                HGF_STAMP(kStream, ph, 3);
             }
             // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of the layer
             const int i = l & 15, kb = l >> 4;
@@ -667,6 +727,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             }
         }
 
+        HGF_STAMP(kStream, ph, 1);
         if (S.nunits > 0) {
             // this parity's rows were last read by the unit wavefront two phases ago
             int spins = 0;
@@ -736,8 +797,10 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (l == 0) __hip_atomic_store(&ctl->h_ready, ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        HGF_STAMP(kStream, ph, 2);
         if (ph + 1 < p.nphases) plan_phase(ph + 1);
     }
+    trace_flush(p, ctl, c, kStream);
 }
 
 // ---- the unit wavefront: finishes the row-blocks this workgroup owns (steps 4, 7, 8) and
@@ -762,9 +825,10 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         const PhaseShape S = shape_of(p, ph, c);
         const StackLayer *L = p.L + S.first;
         const int par = ph & 1;
-        int *tiles = tiles_all + par * kMaxUnits * kMaxFusedM * kTileRows;
+        int *tiles = tiles_all + par * p.tile_par;
         const _Float16 *hs = reinterpret_cast<const _Float16 *>(lds + p.h_off + par * p.h_par);
 
+        HGF_STAMP(kStream + 1, ph, 0);
         // ---- requests that do not depend on the tokens: epilogue operands of my units
         //      (LDS-direct) and the weight scales
         for (int i = 0; i < S.nunits; ++i) {
@@ -787,6 +851,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 if (++spins >= p.lds_polls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
             }
+            HGF_STAMP(kStream + 1, ph, 1);
             // ---- per unit: lane n < 32 owns output row n of the unit for every token
             int rs[kMaxFusedM] = {0, 0, 0, 0};
             float sxv[kMaxFusedM] = {0.f, 0.f, 0.f, 0.f};
@@ -812,6 +877,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                         default: corr = corr_unit<8>(hrow, brow, jl < p.M); break;
                     }
                 }
+                if (i == 0) HGF_STAMP(kStream + 1, ph, 5);
                 int polls = 0;
 #pragma clang loop unroll(disable)
                 while (!failed && lds_load(&ctl->arrived[par][i]) < kStream) {
@@ -821,6 +887,8 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                     }
                     __builtin_amdgcn_s_sleep(1);
                 }
+                if (i == 0) HGF_STAMP(kStream + 1, ph, 2);
+                if (i == S.nunits - 1) HGF_STAMP(kStream + 1, ph, 3);
                 // the unit's sums (and whether a wait of another wavefront has expired), then this
                 // parity's words are ready for the phase after next
                 const int others_failed = __hip_atomic_load(&ctl->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -862,6 +930,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                 }
             }
         }
+        HGF_STAMP(kStream + 1, ph, 4);
         // the other wavefronts may now reuse this parity's words (two phases from here)
         if (l == 0) __hip_atomic_store(&ctl->svc_done, ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 
@@ -877,6 +946,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         }
     }
 
+    trace_flush(p, ctl, c, kStream + 1);
     // ---- the last workgroup to get here advances the launch counter and records what was used
     if (failed && l == 0) __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (l == 0) {
@@ -904,7 +974,7 @@ __global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
     // everything the roles add into or count with starts at zero; afterwards the unit
     // wavefront resets what it has consumed
     int *tiles = reinterpret_cast<int *>(lds + p.tile_off);
-    for (int e = threadIdx.x; e < 2 * kMaxUnits * kMaxFusedM * kTileRows; e += 64 * kWaves) tiles[e] = 0;
+    for (int e = threadIdx.x; e < 2 * p.tile_par; e += 64 * kWaves) tiles[e] = 0;
     for (int e = threadIdx.x; e < (int)(sizeof(Control) / sizeof(int)); e += 64 * kWaves) reinterpret_cast<int *>(&ctl)[e] = 0;
     if (threadIdx.x < 32) reinterpret_cast<int *>(lds + p.jx_off + kMaxFusedM * 1024)[threadIdx.x] = 0;
     __syncthreads();
@@ -926,6 +996,9 @@ __global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
 
 int g_num_cus = 0, g_device = -1;
 int g_wait_limit = 0;                  // 0: the default bounds
+unsigned long long *g_trace = nullptr; // time-stamp buffer of the measurement aid (null: off)
+size_t g_trace_bytes = 0;
+int g_trace_ph0 = 0;
 constexpr size_t kStackLdsMax = 156 * 1024;   // (the compute unit has 160 KiB; the control words are static)
 
 }  // namespace
@@ -957,6 +1030,8 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
         g_num_cus = n > 0 ? n : 1;              // (one workgroup per compute unit even where two would fit:
         g_device = dev;                         //  a workgroup is sized to use a whole unit's LDS)
     }
+    p.trace = nullptr;
+    p.trace_ph0 = g_trace_ph0;
     p.mem_polls = g_wait_limit > 0 ? g_wait_limit : kMemPollsDefault;
     p.lds_polls = g_wait_limit > 0 ? g_wait_limit : kLdsPollsDefault;
     const int M = p.M;
@@ -994,12 +1069,15 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
     p.nwg = nwg;
     const int per_wg = (units_max + nwg - 1) / nwg;
     if (per_wg > kMaxUnits) return false;
+    if (g_trace && g_trace_bytes >= (size_t)nwg * kTraceRoles * kTracePhases * kTraceIds * sizeof(unsigned long long))
+        p.trace = g_trace;
 
     const int kp = round_up(kmax, kTileCols);
     p.xstride = kp + 16;
     size_t off = ((size_t)M * p.xstride + 15) & ~size_t(15);     // quantised tokens at offset 0
     p.tile_off = (int)off;
-    off += (size_t)2 * kMaxUnits * kMaxFusedM * kTileRows * sizeof(int);
+    p.tile_par = per_wg * kMaxFusedM * kTileRows;                 // the units' [token][row] sums, per phase parity
+    off += (size_t)2 * p.tile_par * sizeof(int);
     p.h_off = (int)off;                                           // one set of rows per phase parity
     p.h_par = (int)((size_t)gmax * M * kHsStride * sizeof(_Float16));
     off += (size_t)2 * p.h_par;
@@ -1015,6 +1093,7 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
     if (off + (size_t)kStream * kMinRing * kTileBytes > kStackLdsMax) return false;
     int slots = (int)((kStackLdsMax - off) / ((size_t)kStream * kTileBytes));
     if (slots > kMaxRing) slots = kMaxRing;
+    slots &= ~1;                                                  // the contraction takes the tiles in pairs
     p.ring_off = (int)off;
     p.ring_slots = slots;
     off += (size_t)kStream * slots * kTileBytes;
@@ -1023,6 +1102,13 @@ bool plan_stack(StackParams &p, size_t *lds_bytes)
 }
 
 void set_stack_wait_limit(int tries) { g_wait_limit = tries > 0 ? tries : 0; }
+
+void set_stack_trace(unsigned long long *buf, size_t bytes, int first_phase)
+{
+    g_trace = buf;
+    g_trace_bytes = buf ? bytes : 0;
+    g_trace_ph0 = first_phase > 0 ? first_phase : 0;
+}
 
 hipError_t launch_stack(const StackParams &p, size_t lds_bytes, hipStream_t st)
 {
