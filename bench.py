@@ -200,6 +200,10 @@ def timeline(wl: Workload, ws: hb.Workspace, ph0: int) -> int:
              "slice": ["enter", "own slices stored", "SiLU(A x) in LDS", "own slice multiplied"],
              "unit": ["enter", "SiLU(A x) seen", "first unit complete", "last unit complete", "last unit stored",
                       "first unit's B h done"]}
+    raw = buf.cpu().numpy().astype(np.float64)
+    dclk = raw[:, 10, 3, 2] - raw[:, 10, 0, 2]
+    dwall = (raw[:, 10, 3, 0] - raw[:, 10, 0, 0]) / 100.0
+    print(f"shader clock over the traced phases: {float(np.nanmedian(dclk / dwall)):.0f} MHz")
     for k in range(1, hb.TRACE_PHASES):
         ph = ph0 + k
         prev_done = np.nanmax(t[:, 9, k - 1, 4])
@@ -215,9 +219,15 @@ def timeline(wl: Workload, ws: hb.Workspace, ph0: int) -> int:
             print(f"    {nm:24s} first {med(np.nanmin(c[:, :, i], axis=1)):6.2f}   last {med(np.nanmax(c[:, :, i], axis=1)):6.2f}")
         for i, nm in enumerate(names["slice"]):
             print(f"  slice wavefront  {nm:22s} {med(rel[:, 8, k, i]):6.2f}")
+        allrel = t - prev_done
+        has = ~np.isnan(allrel[:, 8, k, 3])
+        if has.any():
+            print(f"  slice wavefronts with a slice ({int(has.sum())}): last slice multiplied {med(allrel[has, 8, k, 3]):6.2f} "
+                  f"(latest {float(np.nanmax(allrel[has, 8, k, 3])):6.2f}), stored {med(allrel[has, 8, k, 1]):6.2f} "
+                  f"(latest {float(np.nanmax(allrel[has, 8, k, 1])):6.2f})")
         for i, nm in enumerate(names["unit"]):
             print(f"  unit wavefront   {nm:22s} {med(rel[:, 9, k, i]):6.2f}   (latest workgroup {float(np.nanmax(rel[:, 9, k, i])):6.2f})")
-        print(f"  loader 0         first tile requested  {med(rel[:, 10, k, 0]):6.2f}")
+        print(f"  loader 0         first tile requested  {med(rel[:, 10, k, 0]):6.2f}   last {med(rel[:, 10, k, 1]):6.2f}")
     return 0
 
 

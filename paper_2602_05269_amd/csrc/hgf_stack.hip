@@ -40,9 +40,10 @@ constexpr int kStream = 8;             // contracting wavefronts per workgroup (
                                        // MFMAs overlap the other's unpacking of the 2-bit codes
 constexpr int kLoaders = 2;            // loader wavefronts (8, 9): each feeds four contracting ones; 10, 11 serve
 constexpr int kFeed = kStream / kLoaders;
-constexpr int kWaves = kStream + kLoaders + 2;
+constexpr int kUnitWaves = 4;          // unit wavefronts (11..14): unit i of a workgroup goes to number i mod 4
+constexpr int kWaves = kStream + kLoaders + 1 + kUnitWaves;
 constexpr int kWindow = 3;             // groups of kFeed weight tiles a loader keeps in flight
-constexpr int kMinRing = kWindow + 5;  // tiles per contracting wavefront the LDS ring must hold at least (> kWindow; even)
+constexpr int kMinRing = 8;            // tiles per contracting wavefront the LDS ring must hold at least (> kWindow; even)
 constexpr int kMaxRing = 48;
 constexpr int kMaxUnits = 16;          // units per workgroup and phase at most
 constexpr int kLdsPollsDefault = 1 << 22;   // bound of a wait on LDS (about a second)
@@ -56,16 +57,16 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 struct Control {                       // LDS words shared by the two sides; [2]: one set per phase parity
+    alignas(16) int ready[kStream];    // weight tiles of the wavefront's ring that have landed in LDS, in all
+    int consumed[kStream];             // ... and how many of them it has read
     int arrived[2][kMaxUnits];         // contracting wavefronts that have posted the unit (the unit wavefront resets it)
     int rowsum_part[2][kStream][kMaxFusedM];   // sums of the quantised columns each wavefront owns
     float amax_part[2][kStream][kMaxFusedM];   // absmax of those columns
     float sx[2][kMaxFusedM];
     int sync;                          // absmax parts posted, summed over the phases
-    int svc_done;                      // phases whose units the unit wavefront has finished
+    int svc_done[kUnitWaves];          // phases whose units each unit wavefront has finished
     int h_ready;                       // phases whose SiLU(A x) the slice wavefront has put into LDS
     int failed;                        // a wait of a loader, contracting or slice wavefront has expired
-    int ready[kStream];                // weight tiles of the wavefront's ring that have landed in LDS, in all
-    int consumed[kStream];             // ... and how many of them it has read
     unsigned long long stamps[kTraceRoles][kTracePhases][kTraceIds];   // time stamps (only with p.trace set)
 };
 
@@ -99,6 +100,14 @@ __device__ __forceinline__ bool has_sentinel(v4u v)
 __device__ __forceinline__ float exp_fast(float v) { return __builtin_amdgcn_exp2f(v * 1.44269504088896340736f); }
 __device__ __forceinline__ float silu_fast(float h) { return h * __builtin_amdgcn_rcpf(1.0f + exp_fast(-h)); }
 __device__ __forceinline__ float tanh_fast(float a) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_fast(2.0f * a)); }
+// Every unit wavefront has finished the phases before `n`.
+__device__ __forceinline__ bool units_done(const Control *ctl, int n)
+{
+    bool ok = true;
+#pragma unroll
+    for (int u = 0; u < kUnitWaves; ++u) ok = ok && lds_load(&ctl->svc_done[u]) >= n;
+    return ok;
+}
 // What both sides derive from a phase's entry in the kernel arguments (all wave-uniform).
 struct PhaseShape {
     int K, Kp, KT, TPW, TPP, G, first; // TPW: k-tiles per contracting wavefront; TPP: pairs of them; first: the phase's first layer
@@ -145,7 +154,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     // what this phase shares with the unit wavefront was last used two phases ago; looked at
     // here, where the wavefront is about to wait for memory anyway, and waited for (rarely)
     // after the tokens have come
-    bool unit_done = lds_load(&ctl->svc_done) >= ph - 1;
+    bool unit_done = units_done(ctl, ph - 1);
     v4u v[MT][XU];
     int polls = 0;
 #pragma clang loop unroll(disable)
@@ -192,7 +201,7 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     polls = 0;
 #pragma clang loop unroll(disable)
     while (!unit_done && !failed) {
-        unit_done = lds_load(&ctl->svc_done) >= ph - 1;
+        unit_done = units_done(ctl, ph - 1);
         if (++polls >= p.lds_polls) failed = true;
         __builtin_amdgcn_s_sleep(1);
     }
@@ -266,16 +275,33 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
     unsigned char *ring = lds + p.ring_off + (size_t)a * p.ring_slots * kTileBytes;
     const unsigned ready_at = lds_offset(&ctl->ready[a]), cons_at = lds_offset(&ctl->consumed[a]);
     const unsigned failed_at = lds_offset(&ctl->failed);
+    // (one 16-byte write for the four readers, not waited for: LDS takes a wavefront's requests in order)
+    static_assert(kFeed == 4 && offsetof(Control, ready) % 16 == 0, "the four counters are written as one piece");
     auto publish = [&](int n) __attribute__((always_inline)) {
-#pragma unroll
-        for (int f = 0; f < kFeed; ++f) lds_poke(ready_at + 4u * f, n);
+        const v4i four = {n, n, n, n};
+        asm volatile("ds_write_b128 %0, %1" ::"v"(ready_at), "v"(four) : "memory");
     };
-    int n = 0, slot = 0, freed = 0;     // groups issued; ring slot of the next; groups all readers are known to have read
+    // waits until at most k of the groups requested are still on their way
+    auto landed_but = [](int k) __attribute__((always_inline)) {
+        static_assert(kWindow <= 5, "one case per group of the window");
+        switch (k) {
+            case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+            case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * 1) : "memory"); break;
+            case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * 2) : "memory"); break;
+            case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * 3) : "memory"); break;
+            case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * 4) : "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * 5) : "memory"); break;
+        }
+    };
+    // groups issued; ring slot of the next; groups published; groups all readers are known to have read
+    int n = 0, slot = 0, pub = 0, freed = 0;
     bool failed = false;
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
         const StackLayer *L = p.L + S.first;
         if (ld == 0) HGF_STAMP(kStream + 2, ph, 0);
+        if (ld == 0 && p.trace != nullptr && l == 0 && (unsigned)(ph - p.trace_ph0) < (unsigned)kTracePhases)
+            ctl->stamps[kStream + 2][ph - p.trace_ph0][2] = clock64();
         for (int i = 0; i < S.nunits; ++i) {
             const int u = c + i * p.nwg;
             int g = 0, first = 0;
@@ -286,11 +312,12 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
             const rsrc_t wr = make_rsrc(L[g].packed, rows * S.KT * kTileBytes);
             const unsigned row = (unsigned)(u - first) * S.KT;
             for (int j = 0; j < 2 * S.TPP; ++j) {   // (an odd count is padded with a void tile: the contraction goes in pairs)
-                // room in the rings?  While there is none nothing is gained by keeping the
-                // window open: let everything land, publish it, and wait for the readers.
+                // room in the rings?  While there is none, the groups on their way are published one
+                // by one as they land (the readers may be waiting for exactly those), and the next
+                // request goes out as soon as the readers have freed a slot: the readers free slots
+                // two at a time while they contract, and a loader that let everything land before
+                // it looked again would then request one group per trip to memory.
                 if (n - freed >= p.ring_slots) {
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    publish(n);
                     int spins = 0;
 #pragma clang loop unroll(disable)
                     while (!failed) {
@@ -298,8 +325,13 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
 #pragma unroll
                         for (int f = 1; f < kFeed; ++f) freed = min(freed, lds_peek(cons_at + 4u * f));
                         if (n - freed < p.ring_slots) break;
-                        if (++spins >= p.lds_polls || lds_peek(failed_at) != 0) failed = true;
-                        __builtin_amdgcn_s_sleep(2);
+                        if (pub < n) {
+                            landed_but(n - pub - 1);
+                            publish(++pub);
+                        } else {
+                            if (++spins >= p.lds_polls || lds_peek(failed_at) != 0) failed = true;
+                            __builtin_amdgcn_s_sleep(2);
+                        }
                     }
                 }
 #pragma unroll
@@ -311,12 +343,14 @@ __device__ __forceinline__ void loader_wave(const StackParams &p, unsigned char 
                 }
                 ++n;
                 slot = slot + 1 == p.ring_slots ? 0 : slot + 1;
-                if (n > kWindow) {
+                if (n - pub > kWindow) {
                     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kFeed * kWindow) : "memory");
-                    publish(n - kWindow);
+                    pub = n - kWindow;
+                    publish(pub);
                 }
             }
         }
+        if (ld == 0) HGF_STAMP(kStream + 2, ph, 1);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     publish(n);
@@ -524,16 +558,13 @@ __device__ __forceinline__ void job_load(JobRegs &r, const _Float16 *A, int rank
 // The tokens' side of the same batch: 512 columns per token, one 16-byte piece per lane, read
 // from the caller's slot or, once no word is the sentinel, from the exchange region (one
 // request per token and try, so that a try costs little more than the memory's latency).
-// The pieces then pass through 1 KiB of LDS per token into the operand layout: lane (i, kb)
-// holds token i's 16 columns at 64*kp + 16*kb.
-struct JobX {
-    v4u b[kUN][2];
-};
+// The pieces are left in 1 KiB of LDS per token, from where the products read them in the
+// operand layout: lane (i, kb) takes token i's 16 columns at 64*kp + 16*kb.
 template <int MT>
-__device__ __forceinline__ void job_xfetch(JobX &x, unsigned char *jxl, rsrc_t xr, bool ext, int M, int K, int kpb,
+__device__ __forceinline__ void job_xfetch(unsigned char *jxl, rsrc_t xr, bool ext, int M, int K, int kpb,
                                            int kp1, int mem_polls, bool &failed)
 {
-    const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
+    const int l = threadIdx.x & 63;
     const int col = kpb * 64 + l * 8;
     const bool mine = kpb + (l >> 3) < kp1 && col < K;
     v4u v[MT];
@@ -555,19 +586,28 @@ __device__ __forceinline__ void job_xfetch(JobX &x, unsigned char *jxl, rsrc_t x
     }
 #pragma unroll
     for (int m = 0; m < MT; ++m) *reinterpret_cast<v4u *>(jxl + m * 1024 + l * 16) = v[m];
-    const v4u zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int u = 0; u < kUN; ++u) {
-        x.b[u][0] = i < M ? *reinterpret_cast<const v4u *>(jxl + i * 1024 + u * 128 + kb * 32) : zero;
-        x.b[u][1] = i < M ? *reinterpret_cast<const v4u *>(jxl + i * 1024 + u * 128 + kb * 32 + 16) : zero;
-    }
 }
-__device__ __forceinline__ v4f job_mfma(const JobRegs &r, const JobX &x, v4f acc)
+// The products of one batch, the tokens' operands read from LDS half a batch at a time (the
+// rows of A already fill half of the wavefront's registers).
+__device__ __forceinline__ v4f job_mfma(const JobRegs &r, const unsigned char *jxl, int M, v4f acc)
 {
+    const int l = threadIdx.x & 63, i = l & 15, kb = l >> 4;
+    const v4u zero = {0u, 0u, 0u, 0u};
+    const unsigned char *row = jxl + i * 1024 + kb * 32;
 #pragma unroll
-    for (int u = 0; u < kUN; ++u) {
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][0], __builtin_bit_cast(v8h, x.b[u][0]), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u][1], __builtin_bit_cast(v8h, x.b[u][1]), acc, 0, 0, 0);
+    for (int u0 = 0; u0 < kUN; u0 += kUN / 2) {
+        v4u b[kUN / 2][2];
+#pragma unroll
+        for (int u = 0; u < kUN / 2; ++u) {
+            b[u][0] = i < M ? *reinterpret_cast<const v4u *>(row + (u0 + u) * 128) : zero;
+            b[u][1] = i < M ? *reinterpret_cast<const v4u *>(row + (u0 + u) * 128 + 16) : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < kUN / 2; ++u) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u0 + u][0], __builtin_bit_cast(v8h, b[u][0]), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(r.a[u0 + u][1], __builtin_bit_cast(v8h, b[u][1]), acc, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     return acc;
 }
@@ -707,13 +747,12 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                                     (unsigned)p.M * S.K * 2u);
         while (job < njobs) {
             v4f acc = {0.f, 0.f, 0.f, 0.f};
-            JobX jx;
             for (int kpb = kp0; kpb < kp1; kpb += kUN) {
                 if (kpb > kp0) job_load(jr, jA, jrank, S.K, rt, kpb, kp1);
-                if (p.M == 1) job_xfetch<1>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
-                else if (p.M == 2) job_xfetch<2>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
-                else job_xfetch<4>(jx, jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
-                acc = job_mfma(jr, jx, acc);
+                if (p.M == 1) job_xfetch<1>(jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
+                else if (p.M == 2) job_xfetch<2>(jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
+                else job_xfetch<4>(jxl, xr, ext, p.M, S.K, kpb, kp1, p.mem_polls, failed);
+                acc = job_mfma(jr, jxl, p.M, acc);
                 HGF_STAMP(kStream, ph, 3);
             }
             // acc[v]: rank index rt*16 + 4*kb + v of token i  ->  [sp][i][hstride] of the layer
@@ -732,7 +771,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             // this parity's rows were last read by the unit wavefront two phases ago
             int spins = 0;
 #pragma clang loop unroll(disable)
-            while (!failed && lds_load(&ctl->svc_done) < ph - 1) {
+            while (!failed && !units_done(ctl, ph - 1)) {
                 if (++spins >= p.lds_polls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
             }
@@ -742,8 +781,12 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             const int ge1 = ge0 + (rk1 > 0 ? p.M * hs1 / 4 : 0);
             const int ge2 = ge1 + (rk2 > 0 ? p.M * hs2 / 4 : 0);
             const int ge3 = ge2 + (rk3 > 0 ? p.M * hs3 / 4 : 0);
-            for (int f0 = 0; f0 < ge3; f0 += 64) {
-                const int f = f0 + l;
+            // With few sums to collect, 2 or 4 lanes share one and take every 2nd or 4th slice each,
+            // so that more slices fit one batch of requests (a batch costs a trip to memory).
+            const int Q = ge3 <= 16 ? 4 : (ge3 <= 32 ? 2 : 1);
+            const int fl = 64 / Q, q = l / fl;
+            for (int f0 = 0; f0 < ge3; f0 += fl) {
+                const int f = f0 + (l & (fl - 1));
                 // per-lane layer: arithmetic on the comparison results (a chain of selects between
                 // these scalars gets turned into a table in private memory)
                 const int b0 = f >= ge0, b1 = f >= ge1, b2 = f >= ge2;
@@ -760,8 +803,10 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                 const unsigned step = (unsigned)p.M * hstride * 4u;
                 v4f h = {0.f, 0.f, 0.f, 0.f};
                 // the slices of the lane's four sums, eight to a batch of requests (a try costs as
-                // many requests and comparisons as the batch is long), added in slice order
-                for (int s0 = 0; s0 < Sn; s0 += 8) {
+                // many requests and comparisons as the batch is long); each lane adds its slices in
+                // order, then the lanes that share a sum add theirs
+                for (int sb = 0; sb < Sn; sb += 8 * Q) {
+                    const int s0 = sb + q;
                     v4f part[8];
                     int polls = 0;
 #pragma clang loop unroll(disable)
@@ -769,7 +814,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
                         bool ready = true;
 #pragma unroll
                         for (int sl = 0; sl < 8; ++sl) {
-                            const v4u raw = load16_agent(mail, at + (unsigned)(s0 + sl) * step, wanted && s0 + sl < Sn);
+                            const v4u raw = load16_agent(mail, at + (unsigned)(s0 + sl * Q) * step, wanted && s0 + sl * Q < Sn);
                             ready = ready && !has_sentinel(raw);
                             part[sl] = __builtin_bit_cast(v4f, raw);
                         }
@@ -783,7 +828,14 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
 #pragma unroll
                     for (int sl = 0; sl < 8; ++sl) h += part[sl];   // (slices past the last one were read as zero)
                 }
-                if (inside) {
+                if (Q > 1) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        h[v] += __shfl_xor(h[v], 32, 64);
+                        if (Q > 2) h[v] += __shfl_xor(h[v], 16, 64);
+                    }
+                }
+                if (inside && q == 0) {
                     v4h o;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) o[v] = (j + v < rank) ? (_Float16)silu_fast(h[v]) : (_Float16)0.0f;
@@ -805,7 +857,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
 
 // ---- the unit wavefront: finishes the row-blocks this workgroup owns (steps 4, 7, 8) and
 //      hands their outputs on
-__device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c)
+__device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *lds, Control *ctl, int c, int uw)
 {
     const int l = threadIdx.x & 63, jl = l & 31, hf = l >> 5;
     bool failed = false;
@@ -831,7 +883,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         HGF_STAMP(kStream + 1, ph, 0);
         // ---- requests that do not depend on the tokens: epilogue operands of my units
         //      (LDS-direct) and the weight scales
-        for (int i = 0; i < S.nunits; ++i) {
+        for (int i = uw; i < S.nunits; i += kUnitWaves) {
             int g2, n0;
             unit_decode(S, c + i * p.nwg, g2, n0);
             stage_unit(p, L[g2], n0, ustage + i * p.unit_stride);
@@ -843,7 +895,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         const int hs0 = h_stride(L[0].rank), hs1 = h_stride(S.G > 1 ? L[1].rank : 0),
                   hs2 = h_stride(S.G > 2 ? L[2].rank : 0), hs3 = h_stride(S.G > 3 ? L[3].rank : 0);
 
-        if (S.nunits > 0) {
+        if (S.nunits > uw) {
             // ---- SiLU(A x) of the phase is in LDS once the slice wavefront says so
             int spins = 0;
 #pragma clang loop unroll(disable)
@@ -855,7 +907,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
             // ---- per unit: lane n < 32 owns output row n of the unit for every token
             int rs[kMaxFusedM] = {0, 0, 0, 0};
             float sxv[kMaxFusedM] = {0.f, 0.f, 0.f, 0.f};
-            for (int i = 0; i < S.nunits; ++i) {
+            for (int i = uw; i < S.nunits; i += kUnitWaves) {
                 const unsigned char *op = ustage + i * p.unit_stride;
                 int gg, n0;
                 unit_decode(S, c + i * p.nwg, gg, n0);
@@ -896,7 +948,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
 #pragma unroll
                 for (int m = 0; m < kMaxFusedM; ++m) a[m] = tiles[(i * kMaxFusedM + m) * kTileRows + jl];
                 if (others_failed != 0) failed = true;
-                if (i == 0) {           // every contracting wavefront has posted: so are the tokens' sums and scales
+                if (i == uw) {          // every contracting wavefront has posted: so are the tokens' sums and scales
 #pragma unroll
                     for (int m = 0; m < kMaxFusedM; ++m) {
                         rs[m] = 0;
@@ -932,10 +984,10 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         }
         HGF_STAMP(kStream + 1, ph, 4);
         // the other wavefronts may now reuse this parity's words (two phases from here)
-        if (l == 0) __hip_atomic_store(&ctl->svc_done, ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (l == 0) __hip_atomic_store(&ctl->svc_done[uw], ph + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 
         // ---- my share of the sentinels for the launch after this one (once, in the first phase)
-        if (ph == 0) {
+        if (ph == 0 && uw == 0) {
             const rsrc_t oa = make_rsrc(other, prev_act);
             const rsrc_t om = make_rsrc(other + kStackActBytes, prev_mail);
             const v4u s4 = {kSentinel, kSentinel, kSentinel, kSentinel};
@@ -946,9 +998,11 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
         }
     }
 
+    if (failed && l == 0) __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (uw != 0) return;
+    // (the stamps of all unit wavefronts: the others finish their last phase no later than a few polls from here)
     trace_flush(p, ctl, c, kStream + 1);
     // ---- the last workgroup to get here advances the launch counter and records what was used
-    if (failed && l == 0) __hip_atomic_store(p.flags + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (l == 0) {
         const int done = __hip_atomic_fetch_add(p.flags + 5, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (done == p.nwg - 1) {
@@ -981,15 +1035,17 @@ __global__ __launch_bounds__(64 * kWaves) void stack_kernel(const StackParams p)
     if (w < kStream) {
         contract_wave(p, lds, &ctl, c);
     } else if (w < kStream + kLoaders) {
+        __builtin_amdgcn_s_setprio(3);
         loader_wave(p, lds, &ctl, c, w - kStream);
     } else {
         // the two serving wavefronts share their SIMDs with contracting ones and are the ones
         // every other workgroup waits for: they issue first
         if (w == kStream + kLoaders) {
+            __builtin_amdgcn_s_setprio(3);
             slice_wave(p, lds, &ctl, c);
         } else {
             __builtin_amdgcn_s_setprio(3);
-            unit_wave(p, lds, &ctl, c);
+            unit_wave(p, lds, &ctl, c, w - (kStream + kLoaders + 1));
         }
     }
 }
