@@ -91,17 +91,37 @@ __device__ inline v4i widen_codes(uint32_t w)
     return a;
 }
 __device__ inline float silu(float h) { return h / (1.0f + expf(-h)); }
+// Wave-wide reductions with the result in every lane.  The lanes of a row of 16 exchange
+// through the data-parallel-primitive modifiers of the vector ALU (xor 1, xor 2, mirror within
+// 8, mirror within 16: four dependent instructions); the four rows are then combined from
+// scalar reads of one lane each.  (A shuffle through LDS per butterfly step costs an LDS
+// round trip each: six in a row were half a microsecond of the decode chain.)
+template <int CTRL>
+__device__ inline int dpp_move(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
 __device__ inline float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0xB1>(__builtin_bit_cast(int, v))));    // quad_perm [1,0,3,2]
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x4E>(__builtin_bit_cast(int, v))));    // quad_perm [2,3,0,1]
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x141>(__builtin_bit_cast(int, v))));   // row_half_mirror
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x140>(__builtin_bit_cast(int, v))));   // row_mirror
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 __device__ inline int wave_sum(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
 }
 // Sec. 2.2.1 activation quantiser: round half to even, clip to [-127, 127].
 __device__ inline int quant1(float x, float inv)

@@ -219,12 +219,22 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
             const int j = (l >> 4) + 4 * u;
             const int kt = j * kStream + w;
             const v8h x8 = __builtin_bit_cast(v8h, v[m][u]);        // columns past d_in were read as zero
-            uint32_t q2[2] = {0u, 0u};
+            // round(x * inv) by adding 1.5 * 2^23 to the (separately rounded) product: the sum's
+            // spacing is 1, so the addition rounds half to even and leaves the integer, in two's
+            // complement, in the low mantissa bits -- its low byte is the code.  No clipping: |x| is
+            // at most the token's absmax, so the product is at most 127 (1 + 2^-23).  Three byte
+            // permutes gather four codes into a word, a dot product with ones adds them up.
+            uint32_t rb[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = quant1((float)x8[e], inv);
-                sum += q;
-                q2[e >> 2] |= (uint32_t)(q & 0xff) << (8 * (e & 3));
+            for (int e = 0; e < 8; ++e)
+                rb[e] = __builtin_bit_cast(uint32_t, __fadd_rn(__fmul_rn((float)x8[e], inv), 12582912.0f));
+            uint32_t q2[2];
+#pragma unroll
+            for (int hw = 0; hw < 2; ++hw) {
+                const uint32_t lo = __builtin_amdgcn_perm(rb[4 * hw + 1], rb[4 * hw + 0], 0x0c0c0400u);
+                const uint32_t hi = __builtin_amdgcn_perm(rb[4 * hw + 3], rb[4 * hw + 2], 0x0c0c0400u);
+                q2[hw] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                sum = __builtin_amdgcn_sdot4((int)q2[hw], 0x01010101, sum, false);
             }
             // The tile's 128 codes are stored in the order the contraction reads them: column
             // 32 t + 16 h + 4 s + b of the tile at byte (4 h + s) 16 + 4 t + b, so that the sixteen
@@ -475,6 +485,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             return (v4i){(int)(t[0] & m), (int)(t[1] & m), (int)(t[2] & m), (int)(t[3] & m)};
         };
         int ci = 0, cj = 0;
+        const unsigned arrived_at = lds_offset(&ctl->arrived[par][0]);
         // [nb][s]: weight rows 0..15 and 16..31 of the unit, shift s (scale 1, 4, 16, 32); element m: token m
         v4i acc[2][4];
 #pragma unroll
@@ -515,14 +526,22 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
                                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                             }
                 }
-                if (l == 0)
-                    __hip_atomic_fetch_add(&ctl->arrived[par][ci], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                // (LDS takes a wavefront's requests in order: the count follows the sums without a wait,
+                //  which would be one for the operands just requested as well)
+                if (l == 0) asm volatile("ds_add_u32 %0, %1" ::"v"(arrived_at + 4u * (unsigned)ci), "v"(1) : "memory");
                 if (ci == 0) HGF_STAMP(w, ph, 4);
                 if (ci == S.nunits - 1) HGF_STAMP(w, ph, 5);
+                // the next unit starts from zero in the tokens' elements; the others are never read
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                    for (int sh = 0; sh < 4; ++sh) acc[nb][sh] = (v4i){0, 0, 0, 0};
+                    for (int sh = 0; sh < 4; ++sh) acc[nb][sh][0] = 0;
+                if (p.M > 1) {
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                        for (int sh = 0; sh < 4; ++sh) acc[nb][sh][1] = acc[nb][sh][2] = acc[nb][sh][3] = 0;
+                }
                 ++ci;
             }
         };
@@ -532,6 +551,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             if (st + 1 < total) step(o1, o0, st + 1);
         }
         gs += 2 * total;
+
     }
     trace_flush(p, ctl, c, w);
 }
