@@ -437,6 +437,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
         const int total = S.nunits * S.TPP;             // steps: pairs of tiles
         const unsigned long long token_rows = __builtin_amdgcn_ballot_w64(n16 < p.M);
         unsigned long long exec_save;
+        const unsigned cons_at = lds_offset(&ctl->consumed[w]);
         struct Ops {
             v4u t[2];                   // [nb]: the lane's sixteen bytes of codes of row half nb
             v4i x[4];                   // [s]: the lane's token's sixteen columns of shift s
@@ -455,7 +456,7 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
                 int spins = 0;
 #pragma clang loop unroll(disable)
                 do {
-                    known = lds_load(&ctl->ready[w]);
+                    known = __builtin_amdgcn_readfirstlane(lds_load(&ctl->ready[w]));
                     if (++spins >= p.lds_polls) failed = true;
                 } while (known < gs + 2 * st + 2 && !failed);
             }
@@ -470,15 +471,19 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             // the bandwidth, and LDS is what the eight contracting wavefronts share.  The lanes are
             // switched off around the reads by hand: a branch would make the compiler wait here for
             // the requests just made.  It does not see these reads, so the step waits for them itself.
+            // The same lanes tell the loader what it may overwrite: the tiles of the step before
+            // this request's are in registers by now (the caller has waited for them).
             asm volatile("s_mov_b64 %[save], exec\n\t"
                          "s_mov_b64 exec, %[rows]\n\t"
                          "ds_read_b128 %[a], %[at]\n\t"
                          "ds_read_b128 %[b], %[at] offset:16\n\t"
                          "ds_read_b128 %[c], %[at] offset:32\n\t"
                          "ds_read_b128 %[d], %[at] offset:48\n\t"
+                         "ds_write_b32 %[cons], %[done]\n\t"
                          "s_mov_b64 exec, %[save]"
                          : [a] "=&v"(o.x[0]), [b] "=&v"(o.x[1]), [c] "=&v"(o.x[2]), [d] "=&v"(o.x[3]), [save] "=&s"(exec_save)
-                         : [at] "v"(lds_offset(lds + xa)), [rows] "s"(token_rows)
+                         : [at] "v"(lds_offset(lds + xa)), [rows] "s"(token_rows), [cons] "v"(cons_at),
+                           [done] "v"(gs + 2 * min(st, total))
                          : "memory");
         };
         auto masked = [](const v4u t, unsigned m) __attribute__((always_inline)) {
@@ -511,9 +516,6 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
                 acc[nb][3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[3], masked(t3, 0x60606060u), acc[nb][3], 0, 0, 0);
             }
             cj = nj;
-            if ((st & 1) == 1 || nj == 0) {         // tell the loader what it may overwrite
-                if (l == 0) __hip_atomic_store(&ctl->consumed[w], gs + 2 * st + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
             if (nj == 0) {
                 if (l < 16) {           // lanes 0..15 hold tokens 0..3 of weight rows l (nb 0) and 16 + l (nb 1)
 #pragma unroll
@@ -993,7 +995,7 @@ __device__ __forceinline__ void unit_wave(const StackParams &p, unsigned char *l
                         // exchange copy: 32 lanes x 2 bytes gathered into 16 lanes x 4 bytes, padding
                         // columns written as zero so that no sentinel remains in the row
                         const unsigned lo = (unsigned)__builtin_bit_cast(unsigned short, o);
-                        const unsigned nb = (unsigned)__shfl_down((int)lo, 1, 64);
+                        const unsigned nb = (unsigned)dpp_move<0xB1>((int)lo);   // (lane l ^ 1: the right neighbour of an even lane)
                         const unsigned pairw = (n < Lg.N ? lo : 0u) | ((n + 1 < Lg.N ? nb : 0u) << 16);
                         const bool writer = l < 32 && (l & 1) == 0 && n < Npad;
                         __builtin_amdgcn_raw_buffer_store_b32(pairw, act,
