@@ -504,10 +504,15 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             const int nj = cj + 1 == S.TPP ? 0 : cj + 1;
             __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): this step's operands, requested a step ago
             __builtin_amdgcn_sched_barrier(0);
-            operands(on, nj, st + 1);
-            __builtin_amdgcn_sched_barrier(0);      // (the requests stay ahead of the MFMAs)
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
+                // the next step's requests go out between the two halves: the matrix core works on
+                // the first half's products while the wavefront issues them
+                if (nb == 1) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    operands(on, nj, st + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 const v4u t = oc.t[nb];
                 const v4u t3 = {t[0] >> 1, t[1] >> 1, t[2] >> 1, t[3] >> 1};
                 acc[nb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oc.x[0], masked(t, 0x03030303u), acc[nb][0], 0, 0, 0);
