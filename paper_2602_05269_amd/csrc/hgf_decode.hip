@@ -24,12 +24,13 @@ namespace hgf {
 
 namespace {
 
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
 // TG: token groups of 32 (1 or 2).
 template <int TG>
 __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 {
     constexpr int PF = TG == 1 ? 8 : 4;       // weight tiles in flight per wavefront
-    constexpr int XPRE = 4;                         // activation pieces per thread fetched up front
     constexpr int JS = HGF_MAX_RANK / 16;           // steps of the 32x32x16 f16 MFMA over the rank
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -69,20 +70,26 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 #pragma unroll
     for (int u = 0; u < HV; ++u) hpre[u] = buf_load16(hr, (unsigned)(htid + u * hthreads) * 16u, (htid + u * hthreads) * 8 < htotal);
 
-    // ---- (2) the first pieces of the quantised activations (16 bytes each)
+    // ---- (2) the quantised activations of the first stretch of d_in, straight into LDS: one
+    //      request moves up to 1 KiB of one token's row (the rows keep their 16 bytes of padding,
+    //      so a request never crosses a row), the wavefronts take the requests in turn, and all
+    //      of them are in flight together with everything below -- through registers the rows
+    //      took a trip to L2 per eight pieces, which cost 0.7 us per token
     const int cend0 = min(p.CT, p.KT);
     const rsrc_t xr = make_rsrc(p.xq, (unsigned)mcount * p.Kp);
-    v4u xpre[XPRE];
-    {
-        const int pieces_per_row = cend0 * (kTileCols / 16);
-        const int total = mcount * pieces_per_row;
-#pragma unroll
-        for (int u = 0; u < XPRE; ++u) {
-            const int pc = tid + u * nthreads;
-            const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
-            xpre[u] = buf_load16(xr, (unsigned)row * p.Kp + col * 16, pc < total);
+    const int nwaves = nthreads >> 6;
+    auto stage_tokens = [&](int c0, int c1) __attribute__((always_inline)) {
+        const int row_bytes = (c1 - c0) * kTileCols;
+        const int per_row = (row_bytes + 1023) / 1024;
+        for (int i = w; i < mcount * per_row; i += nwaves) {
+            const int row = i / per_row, pc = i - row * per_row;
+            const int at = pc * 1024 + l * 16;
+            if (at < row_bytes)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr_t)(lds + row * p.xstride + pc * 1024), 16,
+                                                         (int)((unsigned)row * p.Kp + (unsigned)c0 * kTileCols + at), 0, 0, 0);
         }
-    }
+    };
+    stage_tokens(0, cend0);
 
     // ---- (3) epilogue operands: gate parameter of the workgroup's rows, B rows and the
     //      token scales of the wavefront that owns the row-block
@@ -163,37 +170,10 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
             for (int t = 0; t < PF; ++t) wq[t] = buf_load16_stream(wr, (unsigned)(kt0 + t * p.KW) * kTileBytes + l * 16);
             __syncthreads();                         // the previous stretch has been consumed
         }
-        {   // stage x_q[:, c0*128 .. cend*128) into LDS, 16 bytes per thread and step
-            const int pieces_per_row = (cend - c0) * (kTileCols / 16);
-            const int total = mcount * pieces_per_row;
-            int first = 0;
-            if (c0 == 0) {
-#pragma unroll
-                for (int u = 0; u < XPRE; ++u) {
-                    const int pc = tid + u * nthreads;
-                    const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
-                    if (pc < total) *reinterpret_cast<v4u *>(lds + row * p.xstride + col * 16) = xpre[u];
-                }
-                first = XPRE * nthreads;
-            }
-            // the rest in batches of eight requests (one at a time would pay a memory round trip
-            // per piece: the time of this kernel would grow with the number of tokens)
-            for (int pc0 = first + tid; pc0 < total; pc0 += 8 * nthreads) {
-                v4u v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int pc = pc0 + u * nthreads;
-                    const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
-                    v[u] = buf_load16(xr, (unsigned)row * p.Kp + (unsigned)c0 * kTileCols + col * 16, pc < total);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int pc = pc0 + u * nthreads;
-                    const int row = pc / pieces_per_row, col = pc - row * pieces_per_row;
-                    if (pc < total) *reinterpret_cast<v4u *>(lds + row * p.xstride + col * 16) = v[u];
-                }
-            }
-        }
+        // x_q[:, c0*128 .. cend*128) is on its way into LDS (the first stretch since the kernel's
+        // start): every wavefront waits for its own requests, then for the others'
+        if (c0 > 0) stage_tokens(c0, cend);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         while (true) {
 #pragma unroll
@@ -356,6 +336,9 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
     }
     p.KW = kw;
     p.RW = p.pair ? 2 : (kw >= 4 ? 1 : 4 / kw);
+    // Many tokens: the staged activations fill most of a compute unit's LDS, so one workgroup is
+    // resident at a time -- then it should be one of eight wavefronts, two row-blocks sharing the stage.
+    if (!p.pair && kw == 4 && (size_t)M * p.Kp > 64 * 1024) p.RW = 2;
     const int nwaves = p.RW * p.KW;
     int wgs = 0;
     for (int g = 0; g < p.G; ++g) {
