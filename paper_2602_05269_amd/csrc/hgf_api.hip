@@ -133,6 +133,7 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
             D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
             D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
             D.h16 = nullptr;
+            D.hpart = nullptr;
             D.y = reinterpret_cast<_Float16 *>(ys[g]);
             D.acc_debug = acc_debug;
             D.N = L.d_out;
@@ -178,7 +179,8 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         D.s_w = L.s_w;
         D.B = reinterpret_cast<const _Float16 *>(L.B_f16);
         D.alpha = reinterpret_cast<const _Float16 *>(L.alpha_f16);
-        D.h16 = reinterpret_cast<_Float16 *>(reinterpret_cast<char *>(ws.h16) + ws.h16_each * g);
+        D.h16 = nullptr;
+        D.hpart = slices;                           // (the main kernel adds the slices of A x itself: no reducing launch)
         D.y = reinterpret_cast<_Float16 *>(ys[g]);
         D.acc_debug = (pair && g == 1) ? acc_debug2 : acc_debug;
         D.N = L.d_out;
@@ -186,12 +188,11 @@ hgf_status run_decode_group(const void *x, int M, const hgf_layer *layers, int G
         D.rank = L.rank;
         D.hstride = h_stride(L.rank > 0 ? L.rank : 1);
     }
-    _Float16 *h16[kMaxGroup];
-    for (int g = 0; g < G; ++g) h16[g] = const_cast<_Float16 *>(dp.L[g].h16);
+    dp.S = prologue_slices(M, K);
     if (ln && launch_ln_quantize(pp.x, M, K, layers[0].ln_gamma, layers[0].ln_beta, layers[0].ln_eps, ws.xq, ws.s_x,
                                  ws.rowsum, st) != hipSuccess)
         return HGF_ERR_DEVICE;
-    if (launch_prologue(pp, h16, st) != hipSuccess) return HGF_ERR_DEVICE;
+    if (launch_prologue(pp, nullptr, st) != hipSuccess) return HGF_ERR_DEVICE;
     ProfileScope prof(0, st);
     return from_hip(launch_decode(dp, K, st));
 }

@@ -1,8 +1,9 @@
 // Decode kernel (up to 64 tokens; the library routes up to 40 here): packed ternary weights x int8 activations, fused with
 // dequantisation, the rank-r up-projection and the gate.
 //
-// Algorithm 1 of the HGF paper, steps 3, 4, 7 and 8:
+// Algorithm 1 of the HGF paper, steps 3, 4, 6, 7 and 8:
 //   acc[m,n] = sum_k T[n,k] x_q[m,k]                       (exact int32)
+//   h[m,j]   = SiLU(sum over the prologue's slices of (A x)[m,j])
 //   y[m,n]   = acc * (s_x[m] s_w) + tanh(alpha[n]) * sum_j B[n,j] h[m,j]
 // The weights are streamed from HBM exactly once with 16-byte loads per lane: one
 // wavefront instruction fetches one 1 KiB tile (32 rows x 128 columns).  The 2-bit codes
@@ -58,17 +59,26 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     const int n0 = rb * kTileRows;                   // this wavefront's 32 output rows
     const bool owner = rb_ok && kw == 0;             // runs the epilogue of the row-block
 
-    // ---- (1) SiLU(A x) of the tokens, fp16 rows of hstride (a small kernel has added the slices
-    //      of the prologue): 16 bytes per thread and request
+    // ---- (1) the prologue's partial sums of A x, [slice][token][hstride] fp32: a thread takes four
+    //      consecutive ranks of one token and adds their slices in order (Alg. 1 step 5 is complete
+    //      with that sum; SiLU, step 6, follows below).  The first eight slices of its first two
+    //      quadruples are requested here, with everything else of the kernel's start.
     //      (pair: each half of the workgroup brings its own layer's rows)
-    constexpr int HV = 2;                            // 512 x 2 x 8 halves >= 64 tokens x 128 ranks
+    constexpr int HV = 2, HS = 8;
     const int hthreads = pair ? nthreads / 2 : nthreads;
     const int htid = pair ? tid - rw * hthreads : tid;
-    const int htotal = L.rank > 0 ? mcount * L.hstride : 0;
-    const rsrc_t hr = make_rsrc(L.h16, (unsigned)htotal * 2u);
-    v4u hpre[HV];
+    const int hquads = L.rank > 0 ? mcount * L.hstride / 4 : 0;
+    const int hwritten = (L.rank + 15) / 16 * 16;    // ranks the prologue's tiles cover (those past the rank: zeros)
+    const unsigned hslice = (unsigned)mcount * L.hstride * 4u;
+    const rsrc_t hr = make_rsrc(L.hpart, L.rank > 0 ? (unsigned)p.S * hslice : 0u);
+    auto hquad_ok = [&](int it) { return it < hquads && (it * 4) % L.hstride < hwritten; };
+    v4f hpre[HV][HS];
 #pragma unroll
-    for (int u = 0; u < HV; ++u) hpre[u] = buf_load16(hr, (unsigned)(htid + u * hthreads) * 16u, (htid + u * hthreads) * 8 < htotal);
+    for (int u = 0; u < HV; ++u)
+#pragma unroll
+        for (int sl = 0; sl < HS; ++sl)
+            hpre[u][sl] = __builtin_bit_cast(v4f, buf_load16(hr, (unsigned)(htid + u * hthreads) * 16u + (unsigned)sl * hslice,
+                                                             hquad_ok(htid + u * hthreads) && sl < p.S));
 
     // ---- (2) the quantised activations of the first stretch of d_in, straight into LDS: one
     //      request moves up to 1 KiB of one token's row (the rows keep their 16 bytes of padding,
@@ -147,11 +157,33 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     // ---- SiLU(A x) of the tokens and tanh(alpha) into LDS
     _Float16 *hs = reinterpret_cast<_Float16 *>(lds + p.h_off + (pair ? rw * p.h_each : 0));
     float *gs = reinterpret_cast<float *>(lds + p.g_off);
+    {
+        // the slices past the eighth (long d_in) and the quadruples past the second (many tokens)
+        // cost further trips to L2
+        auto finish = [&](int it, v4f h, int s0) __attribute__((always_inline)) {
+            for (; s0 < p.S; s0 += HS) {
+                v4f part[HS];
 #pragma unroll
-    for (int u = 0; u < HV; ++u)
-        if ((htid + u * hthreads) * 8 < htotal) *reinterpret_cast<v4u *>(hs + (htid + u * hthreads) * 8) = hpre[u];
-    for (int v = htid + HV * hthreads; v * 8 < htotal; v += hthreads)   // few threads, many tokens
-        *reinterpret_cast<v4u *>(hs + v * 8) = buf_load16(hr, (unsigned)v * 16u);
+                for (int sl = 0; sl < HS; ++sl)
+                    part[sl] = __builtin_bit_cast(v4f, buf_load16(hr, (unsigned)it * 16u + (unsigned)(s0 + sl) * hslice,
+                                                                  hquad_ok(it) && s0 + sl < p.S));
+#pragma unroll
+                for (int sl = 0; sl < HS; ++sl) h += part[sl];
+            }
+            v4h o;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] = (_Float16)silu(h[v]);
+            if (it < hquads) *reinterpret_cast<v4h *>(hs + it * 4) = o;
+        };
+#pragma unroll
+        for (int u = 0; u < HV; ++u) {
+            v4f h = hpre[u][0];
+#pragma unroll
+            for (int sl = 1; sl < HS; ++sl) h += hpre[u][sl];
+            finish(htid + u * hthreads, h, HS);
+        }
+        for (int it = htid + HV * hthreads; it < hquads; it += hthreads) finish(it, (v4f){0.f, 0.f, 0.f, 0.f}, 0);
+    }
     if (tid < p.RW * kTileRows) {
         const int grank = pair ? (tid >= kTileRows ? p.L[1].rank : p.L[0].rank) : L.rank;
         gs[tid] = grank > 0 ? tanhf(alpha_pre) : 0.f;

@@ -204,7 +204,8 @@ struct DecLayer {
     const float *s_w;
     const _Float16 *B;
     const _Float16 *alpha;
-    const _Float16 *h16;     // [M, hstride] fp16 SiLU(A x) (two-launch path), zero padded
+    const _Float16 *h16;     // [M, hstride] fp16 SiLU(A x), zero padded (the base-3 path; the prefill path has its own)
+    const float *hpart;      // [S][M][hstride] fp32 slices of A x from the prologue (the decode kernel adds them itself)
     _Float16 *y;
     int32_t *acc_debug;
     int N, RBn, rank, hstride;
@@ -214,6 +215,7 @@ struct DecodeParams {
     const float *s_x;
     const int32_t *rowsum;
     int M, Kp, KT, G;
+    int S;                   // slices of A x the prologue wrote
     DecLayer L[kMaxGroup];
     int wg_start[kMaxGroup + 1];
     int RW, KW;              // row-blocks per workgroup, wavefronts per row-block (RW*KW = 4 or 8)

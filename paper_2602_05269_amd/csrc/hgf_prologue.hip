@@ -248,6 +248,7 @@ hipError_t launch_prologue(ProParams &p, _Float16 *const *h16, hipStream_t st)
         default: HGF_PRO(4); break;
     }
 #undef HGF_PRO
+    if (h16 == nullptr) return hipGetLastError();   // the consumer adds the slices itself
     ReduceParams rp;
     rp.M = p.M;
     rp.S = p.S;
