@@ -415,7 +415,7 @@ def main() -> int:
             wm = wl.with_tokens(M)
             sm = time_steps(make_runner(wm, ws, use_graph), few, 2)
             c = hbm(wm.bytes / args.blocks, sm / args.blocks)
-            c["path"] = "two-launch decode (prologue, slice reduction, decode_kernel)" if M <= 40 else \
+            c["path"] = "two-launch decode (prologue_kernel, decode_kernel)" if M <= 40 else \
                         "prefill path (prepare_kernel, prefill_kernel)"
             cases[f"config4_block_M{M}_cold"] = c
             del wm
@@ -462,7 +462,8 @@ def main() -> int:
 
         # ---- base-3 packing (1.6 bits per weight) against the 2-bit layout: 16 distinct `up`
         #      layers (4096 -> 11008, r=128) at M=1, one call per layer.  "same_path": the 2-bit
-        #      layer through the same three launches (prologue, slice reduction, main kernel).
+        #      layer through the launch-per-step path as well (prologue, main kernel; the base-3 path has
+        #      the slice reduction as a third launch).
         def b3_cases():
             gen = torch.Generator(device="cuda")
             gen.manual_seed(4500)
@@ -525,7 +526,7 @@ def main() -> int:
         w0 = Workload(0, 8, 1, seed=0, ws=ws)
         s0 = time_steps(make_runner(w0, ws, use_graph), max(20, args.steps), args.warmup)
         cases["config0_single_M8_hot"] = hbm(w0.bytes, s0)
-        cases["config0_single_M8_hot"]["note"] = "0.03 MB of parameters: the latency of three launches, not bandwidth"
+        cases["config0_single_M8_hot"]["note"] = "0.03 MB of parameters: the latency of two launches, not bandwidth"
         del w0
         # 8-layer d=512 stack at M=1: 14.7 MB of parameters, cache-resident ("hot"), launch bound
         w1 = Workload(1, 1, 8, seed=1000, ws=ws)
