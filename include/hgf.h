@@ -151,7 +151,7 @@ typedef struct {
  *   acc_debug int32 [M, d_out] or NULL: receives the exact integer accumulators
  *             sum_k T[n,k] x_q[m,k] of step 3 (for parity tests)
  *
- * M <= 40 runs the bandwidth-bound decode kernels (weights streamed once); larger M
+ * M <= 64 runs the bandwidth-bound decode kernels (weights streamed once); larger M
  * runs the int8 MFMA prefill kernel.  Both give the same integers.  A layer with ln_gamma set
  * takes the fused LayerNorm quantiser as its prologue (one more launch than a layer without;
  * layers with a LayerNorm of their own never share a quantisation in hgf_stack_forward). */
@@ -172,7 +172,7 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
  * down projection (w3), an ordinary hgf_linear_forward.
  *
  *   x_f16           fp16 [M, d_in]
- *   gate, up        host pointers; same d_in and d_out; ranks may differ (for M > 40 they must
+ *   gate, up        host pointers; same d_in and d_out; ranks may differ (for M > 64 they must
  *                   pad to the same multiple-of-32 width, else HGF_ERR_UNSUPPORTED)
  *   z_f16           fp16 [M, d_out], written
  *   amax_out        fp32 [M] or NULL: per-token max_n |z[m, n]| of the stored fp16 values -- the
@@ -239,7 +239,7 @@ hgf_status hgf_linear_forward_b3(const void *x_f16, int M, const hgf_layer *L, v
  * and frees nothing (no hipMalloc, no hipFree, no allocating library routine).
  *
  * Limit: hgf_static_scratch_needed(M, d_in, d_out, rank) <= hgf_static_scratch_bytes(), roughly
- * M * pad128(d_in) + 1 KiB * M (+ 16 KiB * min(M, 40) for M <= 40) + 0.3 MiB: e.g. any d_in at
+ * M * pad128(d_in) + 1 KiB * M (+ 16 KiB * M for M <= 64) + 0.3 MiB: e.g. any d_in at
  * M <= 64, or d_in <= 3072 at M = 2048.  Beyond it: HGF_ERR_WORKSPACE, nothing enqueued.
  * The first call on a GPU (with that GPU current) looks up the array's address there and
  * enqueues two small fill kernels on `stream` that prepare it, as hgf_workspace_init does for a
@@ -303,7 +303,7 @@ hgf_status hgf_probe_mfma_rate(int operand_kind, int iters, double *tops_out, do
  * d_in <= 12288.  level 2 (default): hgf_stack_forward runs whole runs of groups of layers as
  * one persistent launch (activations handed from layer to layer inside the launch), and
  * single groups as level 1; level 1: each group of layers is one persistent launch;
- * level 0: the two-launch path that serves 5..40 tokens.  Results agree bit for bit in the
+ * level 0: the two-launch path that serves 5..64 tokens.  Results agree bit for bit in the
  * integers; the fp16 outputs may differ in the last place (different split of A x). */
 void hgf_set_single_launch(int level);
 

@@ -1,4 +1,4 @@
-// Decode kernel (up to 64 tokens; the library routes up to 40 here): packed ternary weights x int8 activations, fused with
+// Decode kernel (up to 64 tokens): packed ternary weights x int8 activations, fused with
 // dequantisation, the rank-r up-projection and the gate.
 //
 // Algorithm 1 of the HGF paper, steps 3, 4, 6, 7 and 8:
@@ -368,9 +368,14 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
     }
     p.KW = kw;
     p.RW = p.pair ? 2 : (kw >= 4 ? 1 : 4 / kw);
-    // Many tokens: the staged activations fill most of a compute unit's LDS, so one workgroup is
-    // resident at a time -- then it should be one of eight wavefronts, two row-blocks sharing the stage.
-    if (!p.pair && kw == 4 && (size_t)M * p.Kp > 64 * 1024) p.RW = 2;
+    // From a dozen tokens on the staged activations are what a workgroup mostly loads and what
+    // limits how many of them a compute unit holds: then four row-blocks share one stage, two
+    // wavefronts each (measured on the 7B-shape FFN: 47 against 53 us per block at 16 tokens, 58
+    // against 66 at 32, 88 against 103 at 56; at 8 tokens 43 either way).
+    if (!p.pair && kw == 4 && M > 12) {
+        p.KW = 2;
+        p.RW = 4;
+    }
     const int nwaves = p.RW * p.KW;
     int wgs = 0;
     for (int g = 0; g < p.G; ++g) {

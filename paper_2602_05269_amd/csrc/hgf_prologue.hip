@@ -1,4 +1,4 @@
-// Decode prologue (up to 64 tokens; the library routes up to 40 here): one launch that quantises the activations and starts the
+// Decode prologue (up to 64 tokens): one launch that quantises the activations and starts the
 // correction path of every layer reading them.
 //
 // Algorithm 1 of the HGF paper, steps 1-2 (per-token absmax int8 quantisation,
