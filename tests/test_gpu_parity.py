@@ -157,6 +157,39 @@ def test_prefill_group_shares_one_launch(ws):
         assert np.array_equal(got, y1), f"layer {i}: grouped launch and single layer differ"
 
 
+@pytest.mark.parametrize("M", [12, 13, 33, 64])
+def test_decode_group_with_many_row_blocks(M, ws):
+    """Two layers read slot 0 and have 513 row-blocks between them (d_out 8200 and 8190, the
+    second ragged; d_in 520: five k-tiles, the last ragged): the group's launch splits d_in over
+    four wavefronts up to 12 tokens and, from 13 tokens on, gives a workgroup four row-blocks with
+    two wavefronts each (the last workgroup of either layer is ragged); 33 and 64 tokens take two
+    token groups.  Every output against the oracle, accumulators bit for bit against the single
+    layer."""
+    K = 520
+    shapes = [(8200, 16), (8190, 40)]
+    cases, layers = [], []
+    slots = [None] * (len(shapes) + 1)
+    for i, (N, r) in enumerate(shapes):
+        c = synth.make_custom(7800 + i, M, K, N, r, act="student_t3", lora_std=0.05, w_std=0.05)
+        if i == 0:
+            x = c["x"]
+            slots[0] = dev(x)
+        g = GpuLayer(c, ws)
+        g.layer.c.src_slot, g.layer.c.dst_slot = 0, i + 1
+        cases.append(g)
+        layers.append(g.layer)
+        slots[i + 1] = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    hb.hgf_stack_forward(hb.Stack(layers, slots, M), ws)
+    torch.cuda.synchronize()
+    for i, g in enumerate(cases):
+        got = slots[i + 1].cpu().numpy()
+        ref = g.oracle(x)
+        assert_close_fp16(got, ref["y"], f"layer {i}")
+        y1, acc1 = g.forward(x)
+        assert np.array_equal(acc1, ref["acc"])
+        assert_close_fp16(y1, ref["y"], f"layer {i} alone")
+
+
 def test_gate_off_and_rank0_are_the_pure_ternary_layer(ws):
     c = synth.make_custom(77, 8, 512, 256, 32)
     full = GpuLayer(c, ws)
