@@ -415,8 +415,8 @@ def main() -> int:
             wm = wl.with_tokens(M)
             sm = time_steps(make_runner(wm, ws, use_graph), few, 2)
             c = hbm(wm.bytes / args.blocks, sm / args.blocks)
-            c["path"] = "two-launch decode (prologue_kernel, decode_kernel)" if M <= 64 else \
-                        "prefill path (prepare_kernel, prefill_kernel)"
+            c["path"] = "two-launch decode (prologue_kernel, decode_kernel)" if M <= 40 else \
+                        "up + gate: prefill path (prepare_kernel, prefill_kernel); down: two-launch decode"
             cases[f"config4_block_M{M}_cold"] = c
             del wm
 

@@ -151,7 +151,7 @@ typedef struct {
  *   acc_debug int32 [M, d_out] or NULL: receives the exact integer accumulators
  *             sum_k T[n,k] x_q[m,k] of step 3 (for parity tests)
  *
- * M <= 64 runs the bandwidth-bound decode kernels (weights streamed once); larger M
+ * M <= 40 (and up to 64 for layers of few rows) runs the bandwidth-bound decode kernels (weights streamed once); larger M
  * runs the int8 MFMA prefill kernel.  Both give the same integers.  A layer with ln_gamma set
  * takes the fused LayerNorm quantiser as its prologue (one more launch than a layer without;
  * layers with a LayerNorm of their own never share a quantisation in hgf_stack_forward). */
@@ -172,7 +172,7 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
  * down projection (w3), an ordinary hgf_linear_forward.
  *
  *   x_f16           fp16 [M, d_in]
- *   gate, up        host pointers; same d_in and d_out; ranks may differ (for M > 64 they must
+ *   gate, up        host pointers; same d_in and d_out; ranks may differ (for M > 40 they must
  *                   pad to the same multiple-of-32 width, else HGF_ERR_UNSUPPORTED)
  *   z_f16           fp16 [M, d_out], written
  *   amax_out        fp32 [M] or NULL: per-token max_n |z[m, n]| of the stored fp16 values -- the

@@ -61,6 +61,19 @@ hgf_status check_layer(const hgf_layer *L, int M)
 
 hgf_status from_hip(hipError_t e) { return e == hipSuccess ? HGF_OK : HGF_ERR_DEVICE; }
 
+// Which of the two paths a group of layers takes.  Up to 40 tokens the two-launch decode path
+// always; from 41 to 64 (what its kernel handles) only groups of few rows, whose prefill grids
+// would be a handful of 256-row tiles (7B-shape FFN at 64 tokens: the down projection, 4096 rows,
+// takes 52 us on the decode path and 60 on the prefill path; up + gate, 22016 rows, 41 and 33).
+bool takes_decode_path(int M, const hgf_layer *layers, int G, bool pair)
+{
+    if (M <= 40) return true;
+    if (M > kMaxDecodeM || pair) return false;
+    long long rows = 0;
+    for (int g = 0; g < G; ++g) rows += layers[g].d_out;
+    return rows <= 8192;
+}
+
 // Profiling aid: event pairs recorded around main-kernel launches, by kind (0 decode, 1 prefill).
 bool g_profile = false;
 int g_launch_level = 2;      // 0: two launches per group, 1: one persistent launch per group, 2: per stack
@@ -380,7 +393,7 @@ hgf_status hgf_linear_forward(const void *x_f16, int M, const hgf_layer *L, void
     const Workspace ws = carve_workspace(workspace, M, L->d_in, L->d_out, L->rank);
     if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (M <= kMaxDecodeM) {
+    if (takes_decode_path(M, L, 1, false)) {
         void *ys[1] = {y_f16};
         return run_decode_group(x_f16, M, L, 1, ys, acc_debug, ws, st);
     }
@@ -407,12 +420,12 @@ hgf_status hgf_swiglu_forward(const void *x_f16, int M, const hgf_layer *gate, c
     const Workspace ws = carve_workspace(workspace, M, gate->d_in, gate->d_out, rank_max);
     if (workspace_bytes < ws.bytes) return HGF_ERR_WORKSPACE;
     // the prefill kernel stages both layers' SiLU(A x) at one row width
-    if (M > kMaxDecodeM && gate->rank > 0 && up->rank > 0 && h_stride(gate->rank) != h_stride(up->rank))
+    if (M > 40 && gate->rank > 0 && up->rank > 0 && h_stride(gate->rank) != h_stride(up->rank))
         return HGF_ERR_UNSUPPORTED;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const hgf_layer pairL[2] = {*gate, *up};
     void *ys[2] = {nullptr, z_f16};
-    if (M <= kMaxDecodeM)
+    if (takes_decode_path(M, pairL, 2, true))
         return run_decode_group(x_f16, M, pairL, 2, ys, acc_debug_gate, ws, st, true, amax_out, acc_debug_up);
     const PairOut po = {acc_debug_up, amax_out};
     return run_large_group(x_f16, M, pairL, 2, ys, acc_debug_gate, ws, st, &po);
@@ -534,7 +547,7 @@ hgf_status hgf_linear_forward_static(const void *x_f16, int M, const hgf_layer *
     void *ys[1] = {y_f16};
     const bool profiling = g_profile;           // (the profiling aid creates events: not from here)
     g_profile = false;
-    const hgf_status r = M <= kMaxDecodeM ? run_decode_group(x_f16, M, L, 1, ys, acc_debug, ws, st)
+    const hgf_status r = takes_decode_path(M, L, 1, false) ? run_decode_group(x_f16, M, L, 1, ys, acc_debug, ws, st)
                                           : run_large_group(x_f16, M, L, 1, ys, acc_debug, ws, st);
     g_profile = profiling;
     return r;
@@ -592,7 +605,7 @@ hgf_status hgf_stack_forward(const hgf_layer *layers, int n_layers, void *const 
 
     auto run_group = [&](const Group &gr) -> hgf_status {
         const void *x = slots[layers[gr.first].src_slot];
-        if (M <= kMaxDecodeM) {
+        if (takes_decode_path(M, layers + gr.first, gr.G, false)) {
             void *ys[kMaxGroup];
             for (int g = 0; g < gr.G; ++g) ys[g] = slots[layers[gr.first + g].dst_slot];
             return run_decode_group(x, M, layers + gr.first, gr.G, ys, nullptr, ws, st);

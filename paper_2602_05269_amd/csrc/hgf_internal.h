@@ -13,9 +13,10 @@ namespace hgf {
 constexpr int kTileRows = 32;        // a packed tile covers 32 rows ...
 constexpr int kTileCols = 128;       // ... by 128 columns of 2-bit codes
 constexpr int kTileBytes = 1024;
-// Tokens up to which the two-launch decode path is taken: as many as its kernel handles (4 token
-// tiles of 16).  On the 7B-shape FFN block it costs 43 us at 8 tokens, 58 at 32, 82 at 48, 93 at 64,
-// where the prefill path costs the same 91-95 us for anything from 41 to 128.
+// Tokens the two-launch decode path handles (4 token tiles of 16).  It is taken up to 40 tokens
+// always and up to 64 for groups of few rows (takes_decode_path in hgf_api.hip): on the 7B-shape
+// FFN block it costs 43 us at 8 tokens, 58 at 32, 82 at 48, where the prefill path costs the same
+// 91-95 us for anything from 41 to 128.
 constexpr int kMaxDecodeM = 64;
 constexpr int kMaxGroup = 4;         // layers reading the same activations launched together
 

@@ -1,4 +1,4 @@
-// Prefill kernel (more than 64 tokens): the ternary x int8 contraction as a dense int8 MFMA GEMM,
+// Prefill kernel (more than 40 tokens; groups of few rows from 65): the ternary x int8 contraction as a dense int8 MFMA GEMM,
 // fused with dequantisation, the rank-r up-projection and the gate.
 //
 // Algorithm 1 of the HGF paper, steps 3, 4, 7 and 8 (see hgf_decode.hip for the formulas).
