@@ -504,12 +504,13 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             const int nj = cj + 1 == S.TPP ? 0 : cj + 1;
             __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): this step's operands, requested a step ago
             __builtin_amdgcn_sched_barrier(0);
-            // The two contracting wavefronts of a SIMD share its matrix core.  Left alone, the older
-            // one always wins the issue arbitration and the younger one's steps take half as long
-            // again; a wavefront that raises its issue priority for the part of the step that feeds
-            // the matrix core, and lowers it for the rest, makes the two take turns (measured:
-            // 3.7 % on the whole kernel; which of the two parts is the raised one makes no difference).
-            __builtin_amdgcn_s_setprio(1);
+            // The two contracting wavefronts of a SIMD (w and w + 4) share its matrix core.  Left
+            // alone, the older one always wins the issue arbitration and the younger one's steps take
+            // half as long again.  The younger one raises its issue priority for the part of the step
+            // that feeds the matrix core and lowers it for the rest: the two then take turns
+            // (measured on the whole kernel: 2843 -> 3025 GB/s; both wavefronts toggling between 1
+            // and 0, either way round: 2950; a whole step at one priority, alternating: 2855).
+            if (w >= kStream / 2) __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
                 // the next step's requests go out between the two halves: the matrix core works on
