@@ -157,6 +157,19 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     bool unit_done = units_done(ctl, ph - 1);
     v4u v[MT][XU];
     int polls = 0;
+    // Nothing of the layer before can be complete while this workgroup's own row-blocks of it
+    // are not stored, and the lines of that layer's output are polled by every workgroup: the
+    // time a poll takes grows with the polls queued on a line, so polls that cannot succeed only
+    // delay the ones that can (measured: 3040 -> 3120 GB/s).
+    if (!ext) {
+        int spins = 0;
+#pragma clang loop unroll(disable)
+        while (!failed && !units_done(ctl, ph)) {
+            if (++spins >= p.lds_polls) failed = true;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        unit_done = true;
+    }
 #pragma clang loop unroll(disable)
     while (true) {
         bool ready = true;
