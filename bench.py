@@ -217,6 +217,10 @@ def timeline(wl: Workload, ws: hb.Workspace, ph0: int) -> int:
         print("  contracting wavefronts (per workgroup: first / last of the eight; then the median over workgroups)")
         for i, nm in enumerate(names["contract"]):
             print(f"    {nm:24s} first {med(np.nanmin(c[:, :, i], axis=1)):6.2f}   last {med(np.nanmax(c[:, :, i], axis=1)):6.2f}")
+        waited = raw[busy][:, 0:8, k, 6] / 100.0
+        print(f"    waits for weight tiles   {float(np.median(np.sum(raw[busy][:, 0:8, k, 7], axis=1))):6.0f} per workgroup, "
+              f"{float(np.median(np.max(waited, axis=1))):5.2f} us in the wavefront that waited longest (median; "
+              f"mean over wavefronts {float(np.median(np.mean(waited, axis=1))):5.2f} us)")
         for i, nm in enumerate(names["slice"]):
             print(f"  slice wavefront  {nm:22s} {med(rel[:, 8, k, i]):6.2f}")
         allrel = t - prev_done

@@ -318,14 +318,15 @@ void hgf_set_wait_limit(int tries);
 
 /* Measurement aid (host state, not thread-safe): time stamps from inside the whole-stack launch
  * of hgf_stack_forward.  With a device buffer set, every later launch whose workgroups fit it
- * writes, per workgroup, 11 roles x 4 phases x 6 stamps of the device-wide 100 MHz clock (uint64;
- * 0 = not reached): roles 0..7 the contracting wavefronts (0 phase entered, 1 tokens complete,
- * 2 absmax agreed, 3 tokens quantised, 4 first unit contracted, 5 last unit contracted), 8 the
+ * writes, per workgroup, 11 roles x 4 phases x 8 words: stamps of the device-wide 100 MHz clock
+ * (uint64; 0 = not reached): roles 0..7 the contracting wavefronts (0 phase entered, 1 tokens
+ * complete, 2 absmax agreed, 3 tokens quantised, 4 first unit contracted, 5 last unit contracted;
+ * 6 is no stamp but the ticks the wavefront waited for weight tiles to land, 7 its number of such waits), 8 the
  * slice wavefront (0 phase entered, 1 own slices of A x stored, 2 SiLU(A x) in LDS), 9 the unit
  * wavefront (0 phase entered, 1 SiLU(A x) seen, 2 first unit's sums complete, 3 last unit's sums
  * complete, 4 last unit stored), 10 the first loader (0 first weight tile of the phase
  * requested), for the phases first_phase .. first_phase + 3 of the launch.  bytes must cover
- * 256 workgroups (256 * 11 * 4 * 6 * 8).  NULL switches it off.  bench.py --timeline prints the
+ * 256 workgroups (256 * 11 * 4 * 8 * 8).  NULL switches it off.  bench.py --timeline prints the
  * medians. */
 void hgf_set_stack_trace(void *device_buffer, size_t bytes, int first_phase);
 

@@ -169,11 +169,11 @@ def hgf_set_wait_limit(tries: int) -> None:
     lib().hgf_set_wait_limit(int(tries))
 
 
-TRACE_ROLES, TRACE_PHASES, TRACE_IDS = 11, 4, 6
+TRACE_ROLES, TRACE_PHASES, TRACE_IDS = 11, 4, 8
 
 
 def hgf_set_stack_trace(buf: Optional[torch.Tensor], first_phase: int = 0) -> None:
-    """Time stamps of the whole-stack launch into `buf` (int64 [256, 11, 4, 6] on the device); None: off."""
+    """Time stamps of the whole-stack launch into `buf` (int64 [256, 11, 4, 8] on the device); None: off."""
     if buf is None:
         lib().hgf_set_stack_trace(None, 0, 0)
     else:

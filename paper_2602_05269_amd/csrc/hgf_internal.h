@@ -280,7 +280,7 @@ struct StackPhase {                                    // 24 bytes
 // consecutive phases; the words leave through LDS at the end of the launch.
 constexpr int kTraceRoles = 11;       // contracting wavefronts 0..7, slice wavefront, unit wavefront, loader 0
 constexpr int kTracePhases = 4;
-constexpr int kTraceIds = 6;
+constexpr int kTraceIds = 8;
 struct StackParams {
     int M, nphases, nwg, trace_ph0;   // trace_ph0: first traced phase
     unsigned long long *trace;        // null, or [nwg][kTraceRoles][kTracePhases][kTraceIds] time stamps

@@ -136,6 +136,17 @@ __device__ __forceinline__ PhaseShape shape_of(const StackParams &p, int ph, int
     s.nunits = c < s.units ? (s.units - c + p.nwg - 1) / p.nwg : 0;
     return s;
 }
+// fp32 product of fp16 half H (0: low, 1: high) of `packed` and the fp32 `scale`, rounded once
+// (an FMA whose addend is zero), without a conversion instruction of its own
+template <int H>
+__device__ __forceinline__ float scaled_half(uint32_t packed, float scale)
+{
+    float r;
+    if (H == 0) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(scale));
+    else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(scale));
+    return r;
+}
+
 // ------------------------------------------------------------------ loaders and contracting wavefronts
 // Per-token absmax int8 quantisation (Sec. 2.2.1) of the columns wavefront w contracts: the
 // k-tiles w, w+8, ... (128 columns each).  The columns come from the caller's slot or, once
@@ -231,16 +242,20 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
             if (4 * u >= S.TPW) continue;
             const int j = (l >> 4) + 4 * u;
             const int kt = j * kStream + w;
-            const v8h x8 = __builtin_bit_cast(v8h, v[m][u]);        // columns past d_in were read as zero
+            // (columns past d_in were read as zero)
             // round(x * inv) by adding 1.5 * 2^23 to the (separately rounded) product: the sum's
             // spacing is 1, so the addition rounds half to even and leaves the integer, in two's
             // complement, in the low mantissa bits -- its low byte is the code.  No clipping: |x| is
             // at most the token's absmax, so the product is at most 127 (1 + 2^-23).  Three byte
             // permutes gather four codes into a word, a dot product with ones adds them up.
+            // The product comes from the mixed-precision FMA with a zero addend: it widens the fp16
+            // operand itself and rounds once, which is the fp32 product, in one instruction instead of two.
             uint32_t rb[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                rb[e] = __builtin_bit_cast(uint32_t, __fadd_rn(__fmul_rn((float)x8[e], inv), 12582912.0f));
+            for (int d = 0; d < 4; ++d) {
+                rb[2 * d] = __builtin_bit_cast(uint32_t, __fadd_rn(scaled_half<0>(v[m][u][d], inv), 12582912.0f));
+                rb[2 * d + 1] = __builtin_bit_cast(uint32_t, __fadd_rn(scaled_half<1>(v[m][u][d], inv), 12582912.0f));
+            }
             uint32_t q2[2];
 #pragma unroll
             for (int hw = 0; hw < 2; ++hw) {
@@ -466,12 +481,18 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
         auto operands = [&](Ops &o, int jp, int st) __attribute__((always_inline)) {
             const bool real = st < total;
             if (__builtin_expect(real && known < gs + 2 * st + 2, 0)) {
+                const bool traced = p.trace != nullptr && (unsigned)(ph - p.trace_ph0) < (unsigned)kTracePhases;
+                const unsigned long long since = traced ? wall_clock64() : 0ull;
                 int spins = 0;
 #pragma clang loop unroll(disable)
                 do {
                     known = __builtin_amdgcn_readfirstlane(lds_load(&ctl->ready[w]));
                     if (++spins >= p.lds_polls) failed = true;
                 } while (known < gs + 2 * st + 2 && !failed);
+                if (traced && l == 0) {     // ids 6, 7: clock ticks spent waiting for tiles to land, and the waits
+                    ctl->stamps[w][ph - p.trace_ph0][6] += wall_clock64() - since;
+                    ctl->stamps[w][ph - p.trace_ph0][7] += 1;
+                }
             }
             const unsigned char *ta = tlane + slot * kTileBytes;        // (the ring holds an even number of tiles)
             o.t[0] = *reinterpret_cast<const v4u *>(ta);
@@ -1115,6 +1136,7 @@ unsigned long long *g_trace = nullptr; // time-stamp buffer of the measurement a
 size_t g_trace_bytes = 0;
 int g_trace_ph0 = 0;
 constexpr size_t kStackLdsMax = 156 * 1024;   // (the compute unit has 160 KiB; the control words are static)
+static_assert(sizeof(Control) <= 160 * 1024 - kStackLdsMax, "the control words must fit beside the dynamic part");
 
 }  // namespace
 
