@@ -215,6 +215,40 @@ def test_zero_token_and_extreme_accumulators(ws):
     g.check_forward(x)
 
 
+@pytest.mark.parametrize("M", [1, 2, 4, 8, 33, 100])
+def test_tokens_of_fp16_subnormals(M, ws):
+    """Tokens whose every value is an fp16 subnormal (below 6.1e-5), one of them below the
+    quantiser's floor of 1e-5 for the absmax: the scale 127 / amax is then in the millions and the
+    codes are only right if no stage flushes the subnormal inputs.  Through the single-layer entry
+    point and as the first layer of a list (M <= 4: the whole-stack launch): the oracle's integers."""
+    rng = np.random.default_rng(9100 + M)
+    c = synth.make_custom(9100 + M, M, 520, 256, 16, lora_std=0.05, w_std=50.0)   # large s_w: outputs in fp16's normal range
+    x = (rng.standard_normal((M, 520)) * 2e-5).clip(-6e-5, 6e-5).astype(np.float16)
+    x[M // 2] = (rng.standard_normal(520) * 2e-6).astype(np.float16)       # absmax below the floor
+    assert np.abs(x.astype(np.float32)).max() < 6.1e-5 and np.count_nonzero(x) > x.size // 2
+    g = GpuLayer(c, ws)
+    y, acc = g.forward(x)
+    ref = g.oracle(x)
+    assert np.abs(ref["acc"]).max() > 50
+    assert np.array_equal(acc, ref["acc"])
+    g.check_forward(x)
+    c2 = synth.make_custom(9200 + M, M, 256, 128, 8, lora_std=0.05, w_std=0.05)
+    g2 = GpuLayer(c2, ws)
+    g.layer.c.src_slot, g.layer.c.dst_slot = 0, 1
+    g2.layer.c.src_slot, g2.layer.c.dst_slot = 1, 2
+    slots = [dev(x), torch.zeros((M, 256), dtype=torch.float16, device="cuda"),
+             torch.zeros((M, 128), dtype=torch.float16, device="cuda")]
+    hb.hgf_stack_forward(hb.Stack([g.layer, g2.layer], slots, M), ws)
+    torch.cuda.synchronize()
+    host = [t.cpu().numpy() for t in slots]
+    assert_close_fp16(host[1], ref["y"], "first layer of the list")
+    big = np.abs(ref["y"]) > 1e-4           # a wrong or flushed code moves these by percents
+    assert big.mean() > 0.3
+    assert np.all(np.abs(host[1].astype(np.float64) - ref["y"])[big] <= 5e-3 * np.abs(ref["y"])[big])
+    assert np.all(np.abs(y.astype(np.float64) - ref["y"])[big] <= 5e-3 * np.abs(ref["y"])[big])
+    assert_close_fp16(host[2], g2.oracle(host[1])["y"], "second layer of the list")
+
+
 def test_repeated_calls_reuse_the_workspace(ws):
     """The workspace carries nothing from one call into the next: the same call twice, then a different
     shape, all on one workspace, give the oracle's integers every time."""
