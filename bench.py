@@ -415,11 +415,12 @@ def main() -> int:
                                       "non_finite": int((~torch.isfinite(last)).sum())}
         # ---- config 4 at more tokens: the same 32 blocks of weights (cold), per FFN block
         cases["config4_block_M1_cold"] = hbm(wl.bytes / args.blocks, sec / args.blocks)
-        for M in (8, 32, 64):
+        for M in (2, 4, 8, 32, 64):
             wm = wl.with_tokens(M)
             sm = time_steps(make_runner(wm, ws, use_graph), few, 2)
             c = hbm(wm.bytes / args.blocks, sm / args.blocks)
-            c["path"] = "two-launch decode (prologue_kernel, decode_kernel)" if M <= 40 else \
+            c["path"] = "whole-stack launches (stack_kernel)" if M <= 4 else \
+                        "two-launch decode (prologue_kernel, decode_kernel)" if M <= 40 else \
                         "up + gate: prefill path (prepare_kernel, prefill_kernel); down: two-launch decode"
             cases[f"config4_block_M{M}_cold"] = c
             del wm

@@ -136,6 +136,7 @@ __device__ __forceinline__ PhaseShape shape_of(const StackParams &p, int ph, int
     s.nunits = c < s.units ? (s.units - c + p.nwg - 1) / p.nwg : 0;
     return s;
 }
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 // fp32 product of fp16 half H (0: low, 1: high) of `packed` and the fp32 `scale`, rounded once
 // (an FMA whose addend is zero), without a conversion instruction of its own
 template <int H>
@@ -204,15 +205,17 @@ __device__ __forceinline__ void fetch_quantise(const StackParams &p, const Phase
     HGF_STAMP(w, ph, 1);
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-        float amax = 0.0f;
+        // (the maximum of fp16 magnitudes is exact in fp16: two at a time, widened once at the end;
+        //  the instruction by hand: the builtin adds a canonicalising maximum per operand)
+        uint32_t mx = 0u;
 #pragma unroll
         for (int u = 0; u < XU; ++u) {
             if (4 * u >= S.TPW) continue;           // (no k-turn that far in this phase: nothing was read)
-            const v8h a = __builtin_elementwise_abs(__builtin_bit_cast(v8h, v[m][u]));
 #pragma unroll
-            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, (float)a[e]);
+            for (int d = 0; d < 4; ++d) asm("v_pk_max_f16 %0, %1, %2" : "=v"(mx) : "v"(mx), "v"(v[m][u][d] & 0x7fff7fffu));
         }
-        amax = wave_max(amax);
+        const v2h mx2 = __builtin_bit_cast(v2h, mx);
+        float amax = wave_max(fmaxf((float)mx2[0], (float)mx2[1]));
         if (l == 0) ctl->amax_part[par][w][m] = amax;
     }
     if (l == 0) __hip_atomic_fetch_add(&ctl->sync, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
