@@ -31,7 +31,7 @@ typedef __attribute__((address_space(3))) void *lds_ptr_t;
 template <int TG>
 __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 {
-    constexpr int PF = TG == 1 ? 8 : 4;       // weight tiles in flight per wavefront
+    constexpr int PF = TG == 1 ? 6 : 4;       // weight tiles in flight per wavefront (4 ... 10 measured within 3 %; 16: 10 % slower)
     constexpr int JS = HGF_MAX_RANK / 16;           // steps of the 32x32x16 f16 MFMA over the rank
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
