@@ -27,8 +27,10 @@ namespace {
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
-// TG: token groups of 32 (1 or 2).
-template <int TG>
+// TG: token groups of 32 (1 or 2).  PAIR: the gated pair of two layers (a constant of the kernel:
+// the single wavefront that finishes a row-block runs the epilogue, and what it does not need
+// should not be in its way).
+template <int TG, bool PAIR>
 __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
 {
     constexpr int PF = TG == 1 ? 6 : 4;       // weight tiles in flight per wavefront (4 ... 10 measured within 3 %; 16: 10 % slower)
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     // this workgroup's layer: every candidate is read at a fixed kernel-argument offset (one
     // batch of scalar loads) and selected, instead of a dependent load at a computed offset
     const int rw = w / p.KW, kw = w % p.KW;
-    const bool pair = p.pair != 0;
+    constexpr bool pair = PAIR;
     DecLayer L = p.L[0];
     int wg0 = 0;
 #pragma unroll
@@ -407,18 +409,25 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
 
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     static const hipError_t attr = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<2>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        const void *const kernels[] = {reinterpret_cast<const void *>(&decode_kernel<1, false>),
+                                       reinterpret_cast<const void *>(&decode_kernel<2, false>),
+                                       reinterpret_cast<const void *>(&decode_kernel<1, true>),
+                                       reinterpret_cast<const void *>(&decode_kernel<2, true>)};
+        for (const void *k : kernels) {
+            const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
     }();
     if (attr != hipSuccess) return attr;
     const dim3 grid(wgs), block(64 * nwaves);
-    if (tgroups == 1)
-        hipLaunchKernelGGL(decode_kernel<1>, grid, block, lds, st, p);
-    else
-        hipLaunchKernelGGL(decode_kernel<2>, grid, block, lds, st, p);
+    if (p.pair) {
+        if (tgroups == 1) hipLaunchKernelGGL((decode_kernel<1, true>), grid, block, lds, st, p);
+        else hipLaunchKernelGGL((decode_kernel<2, true>), grid, block, lds, st, p);
+    } else {
+        if (tgroups == 1) hipLaunchKernelGGL((decode_kernel<1, false>), grid, block, lds, st, p);
+        else hipLaunchKernelGGL((decode_kernel<2, false>), grid, block, lds, st, p);
+    }
     return hipGetLastError();
 }
 
