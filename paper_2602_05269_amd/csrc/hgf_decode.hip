@@ -239,18 +239,30 @@ __global__ __launch_bounds__(512) void decode_kernel(DecodeParams p)
     // ---- add the KW partial tiles of a row-block: its first wavefront ends up owning it
     if (p.KW > 1) {
         __syncthreads();                             // the activations in LDS are no longer needed
-        v16i *red = reinterpret_cast<v16i *>(lds);
+        // (a partial tile as four pieces of 16 bytes per lane, piece by piece across the lanes:
+        //  whole accumulators side by side, 64 bytes apart, put four lanes on every bank)
+        v4i *red = reinterpret_cast<v4i *>(lds);
         const int slot0 = w - rw - 1;               // the non-owning wavefronts, densely numbered
         if (kw > 0) {
 #pragma unroll
-            for (int tg = 0; tg < TG; ++tg) red[((slot0 * TG) + tg) * 64 + l] = acc[tg];
+            for (int tg = 0; tg < TG; ++tg)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    red[(((slot0 * TG) + tg) * 4 + c) * 64 + l] =
+                        (v4i){acc[tg][4 * c], acc[tg][4 * c + 1], acc[tg][4 * c + 2], acc[tg][4 * c + 3]};
         }
         __syncthreads();
         if (kw > 0 && !pair) return;
         if (kw == 0) {
             for (int o = 1; o < p.KW; ++o) {
 #pragma unroll
-                for (int tg = 0; tg < TG; ++tg) acc[tg] += red[(((slot0 + o) * TG) + tg) * 64 + l];
+                for (int tg = 0; tg < TG; ++tg)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const v4i t = red[((((slot0 + o) * TG) + tg) * 4 + c) * 64 + l];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[tg][4 * c + i] += t[i];
+                    }
             }
         }
     }
