@@ -546,8 +546,9 @@ __device__ __forceinline__ void contract_wave(const StackParams &p, unsigned cha
             // half as long again.  The younger one raises its issue priority for the part of the step
             // that feeds the matrix core and lowers it for the rest: the two then take turns
             // (measured on the whole kernel: 2843 -> 3025 GB/s; both wavefronts toggling between 1
-            // and 0, either way round: 2950; a whole step at one priority, alternating: 2855).
-            if (w >= kStream / 2) __builtin_amdgcn_s_setprio(2);
+            // and 0, either way round: 2950; a whole step at one priority, alternating: 2855; the level
+            // it raises to matters little: 1, 2 and 3 within 0.6 %, 3 ahead).
+            if (w >= kStream / 2) __builtin_amdgcn_s_setprio(3);
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
                 // the next step's requests go out between the two halves: the matrix core works on
