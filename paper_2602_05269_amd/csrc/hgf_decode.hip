@@ -378,7 +378,11 @@ hipError_t launch_decode(DecodeParams &p, int d_in, hipStream_t st)
     if (p.pair) {
         // a workgroup per row-block index, two sets of up to four wavefronts (gate rows, up rows)
         if (p.G != 2 || p.L[0].N != p.L[1].N) return hipErrorInvalidValue;
-        if (kw > 4) kw = 4;
+        // (up to 16 tokens two per set: workgroups of 256 threads, several to a compute unit and
+        //  the whole grid in one round -- 21.0 against 25.7 us for the 7B-shape pair at one token, 25.9
+        //  against 30.4 at 16; from 24 tokens on the staged tokens make four per set the faster shape)
+        const int per_set = M <= 16 ? 2 : 4;
+        if (kw > per_set) kw = per_set;
     }
     p.KW = kw;
     p.RW = p.pair ? 2 : (kw >= 4 ? 1 : 4 / kw);
